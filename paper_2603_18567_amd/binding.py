@@ -1,0 +1,133 @@
+"""ctypes binding of libttt_attn.so: same names as include/ttt_attn.h, argument marshalling only.
+
+Every step of the path runs in the HIP kernels; PyTorch supplies device memory and the stream.
+There is no fallback: if the library has not been built the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from .build import LIB_PATH
+
+TTT_OK, TTT_ERR_INVALID_ARG, TTT_ERR_UNSUPPORTED, TTT_ERR_WORKSPACE, TTT_ERR_HIP = 0, -1, -2, -3, -4
+TTT_F32, TTT_BF16 = 0, 1
+TTT_PASS_FWD, TTT_PASS_BWD, TTT_PASS_BWD_ACCUM = 0, 1, 2
+TTT_MAX_STEPS = 32
+
+EXPORTS = ("ttt_attn_workspace_bytes", "ttt_attn_fwd", "ttt_attn_bwd", "ttt_attn_last_error")
+
+
+class TttAttnParams(ctypes.Structure):
+    _fields_ = [
+        ("dtype", ctypes.c_int32), ("k", ctypes.c_int32),
+        ("step_begin", ctypes.c_int32), ("step_end", ctypes.c_int32),
+        ("total_tokens", ctypes.c_int32), ("n_docs", ctypes.c_int32),
+        ("hq", ctypes.c_int32), ("hkv", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float),
+        ("q_stride_token", ctypes.c_int64), ("q_stride_head", ctypes.c_int64),
+        ("kv_stride_token", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64),
+    ]
+
+
+class TttAttnError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"ttt_attn error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library():
+    """Load the in-tree shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2603_18567_amd.build` "
+                "(there is no CPU or PyTorch fallback for TTT attention)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, pp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)
+        lib.ttt_attn_workspace_bytes.restype = ctypes.c_size_t
+        lib.ttt_attn_workspace_bytes.argtypes = [ctypes.POINTER(TttAttnParams), ctypes.c_int]
+        lib.ttt_attn_fwd.restype = ctypes.c_int
+        lib.ttt_attn_fwd.argtypes = [ctypes.POINTER(TttAttnParams), pp, pp, pp, vp, vp, pp, pp,
+                                     vp, ctypes.c_size_t, vp]
+        lib.ttt_attn_bwd.restype = ctypes.c_int
+        lib.ttt_attn_bwd.argtypes = [ctypes.POINTER(TttAttnParams), pp, pp, pp, pp, pp, pp, vp, vp,
+                                     pp, pp, pp, ctypes.c_int, vp, ctypes.c_size_t, vp]
+        lib.ttt_attn_last_error.restype = ctypes.c_char_p
+        lib.ttt_attn_last_error.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def ttt_attn_last_error() -> str:
+    return load_library().ttt_attn_last_error().decode()
+
+
+def _ptr_array(tensors, k):
+    arr = (ctypes.c_void_p * k)()
+    for i in range(k):
+        t = tensors[i] if tensors is not None and i < len(tensors) else None
+        arr[i] = None if t is None else t.data_ptr()
+    return arr
+
+
+def make_params(q_like, kv_like, k, step_begin, step_end, cu_seqlens_host, softmax_scale) -> TttAttnParams:
+    """Parameter block from one [T,hq,d] and one [T,hkv,d] tensor (shapes, strides, dtype)."""
+    T, hq, d = q_like.shape
+    hkv = kv_like.shape[1]
+    assert q_like.stride(2) == 1 and kv_like.stride(2) == 1, "head_dim must be contiguous"
+    dt = {torch.float32: TTT_F32, torch.bfloat16: TTT_BF16}[q_like.dtype]
+    return TttAttnParams(dt, k, step_begin, step_end, T, len(cu_seqlens_host) - 1, hq, hkv, d,
+                         float(softmax_scale), q_like.stride(0), q_like.stride(1),
+                         kv_like.stride(0), kv_like.stride(1))
+
+
+def ttt_attn_workspace_bytes(params: TttAttnParams, which_pass: int) -> int:
+    lib = load_library()
+    n = lib.ttt_attn_workspace_bytes(ctypes.byref(params), which_pass)
+    if n == 0:
+        raise TttAttnError(TTT_ERR_INVALID_ARG, ttt_attn_last_error())
+    return int(n)
+
+
+def _stream_ptr(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _cu_host_array(cu_seqlens_host):
+    vals = [int(x) for x in cu_seqlens_host]
+    return (ctypes.c_int32 * len(vals))(*vals)
+
+
+def ttt_attn_fwd(params, q, k, v, cu_seqlens_dev, cu_seqlens_host, o, lse, workspace, stream=None):
+    """q,k,v,o,lse: lists (length params.k; None where a step is not needed) of device tensors."""
+    lib = load_library()
+    K = params.k
+    rc = lib.ttt_attn_fwd(ctypes.byref(params), _ptr_array(q, K), _ptr_array(k, K), _ptr_array(v, K),
+                          ctypes.c_void_p(cu_seqlens_dev.data_ptr()), _cu_host_array(cu_seqlens_host),
+                          _ptr_array(o, K), _ptr_array(lse, K),
+                          ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                          _stream_ptr(stream))
+    if rc != TTT_OK:
+        raise TttAttnError(rc, ttt_attn_last_error())
+
+
+def ttt_attn_bwd(params, q, k, v, o, lse, d_o, cu_seqlens_dev, cu_seqlens_host, dq, dk, dv,
+                 accumulate_dkv, workspace, stream=None):
+    lib = load_library()
+    K = params.k
+    rc = lib.ttt_attn_bwd(ctypes.byref(params), _ptr_array(q, K), _ptr_array(k, K), _ptr_array(v, K),
+                          _ptr_array(o, K), _ptr_array(lse, K), _ptr_array(d_o, K),
+                          ctypes.c_void_p(cu_seqlens_dev.data_ptr()), _cu_host_array(cu_seqlens_host),
+                          _ptr_array(dq, K), _ptr_array(dk, K), _ptr_array(dv, K), int(accumulate_dkv),
+                          ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                          _stream_ptr(stream))
+    if rc != TTT_OK:
+        raise TttAttnError(rc, ttt_attn_last_error())

@@ -1,0 +1,241 @@
+// C ABI of the TTT attention library: argument validation, workspace layout, launch sequencing.
+// No arithmetic of the method lives here; see include/ttt_attn.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/ttt_attn.h"
+#include "ttt_args.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Everything that can be checked from the parameter block alone.
+int check_params(const ttt_attn_params* p) {
+    if (!p) return fail(TTT_ERR_INVALID_ARG, "params is NULL");
+    if (p->dtype != TTT_F32 && p->dtype != TTT_BF16) return fail(TTT_ERR_UNSUPPORTED, "dtype %d is not TTT_F32/TTT_BF16", p->dtype);
+    if (p->head_dim != 64 && p->head_dim != 128) return fail(TTT_ERR_UNSUPPORTED, "head_dim %d is not 64 or 128", p->head_dim);
+    if (p->k < 1 || p->k > TTT_MAX_STEPS) return fail(TTT_ERR_INVALID_ARG, "k=%d outside 1..%d", p->k, TTT_MAX_STEPS);
+    if (p->step_begin < 0 || p->step_end > p->k || p->step_begin > p->step_end)
+        return fail(TTT_ERR_INVALID_ARG, "step range [%d,%d) not inside [0,%d)", p->step_begin, p->step_end, p->k);
+    if (p->total_tokens < 0 || p->n_docs < 0) return fail(TTT_ERR_INVALID_ARG, "negative total_tokens or n_docs");
+    if (p->total_tokens > 0 && p->n_docs == 0) return fail(TTT_ERR_INVALID_ARG, "tokens without documents");
+    if (p->hq < 1 || p->hkv < 1 || p->hq % p->hkv != 0)
+        return fail(TTT_ERR_INVALID_ARG, "hq=%d must be a positive multiple of hkv=%d", p->hq, p->hkv);
+    if (!(p->softmax_scale > 0.f) || !std::isfinite(p->softmax_scale))
+        return fail(TTT_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
+    const int64_t st[4] = {p->q_stride_token, p->q_stride_head, p->kv_stride_token, p->kv_stride_head};
+    for (int i = 0; i < 4; ++i)
+        if (st[i] < p->head_dim || st[i] % 8 != 0)
+            return fail(TTT_ERR_INVALID_ARG, "stride %d = %lld must be >= head_dim and a multiple of 8 elements", i, (long long)st[i]);
+    return TTT_OK;
+}
+
+int check_cu(const ttt_attn_params* p, const int32_t* cu_dev, const int32_t* cu_host) {
+    if (!cu_dev || !cu_host) return fail(TTT_ERR_INVALID_ARG, "cu_seqlens pointer is NULL");
+    if (cu_host[0] != 0) return fail(TTT_ERR_INVALID_ARG, "cu_seqlens[0] = %d, expected 0", cu_host[0]);
+    for (int r = 0; r < p->n_docs; ++r)
+        if (cu_host[r + 1] < cu_host[r]) return fail(TTT_ERR_INVALID_ARG, "cu_seqlens decreases at document %d", r);
+    if (cu_host[p->n_docs] != p->total_tokens)
+        return fail(TTT_ERR_INVALID_ARG, "cu_seqlens[n_docs] = %d, expected total_tokens = %d", cu_host[p->n_docs], p->total_tokens);
+    return TTT_OK;
+}
+
+int check_ptr(const void* p, const char* what, int step) {
+    if (!p) return fail(TTT_ERR_INVALID_ARG, "%s[%d] is NULL but the call needs it", what, step);
+    if (!aligned16(p)) return fail(TTT_ERR_INVALID_ARG, "%s[%d] is not 16-byte aligned", what, step);
+    return TTT_OK;
+}
+
+struct Layout {
+    size_t tok_start, tok_end, delta, dk0, dv0, dkl, dvl, total;
+};
+
+Layout make_layout(const ttt_attn_params* p, int pass) {
+    Layout L{};
+    const size_t T = (size_t)p->total_tokens;
+    size_t off = 0;
+    L.tok_start = off; off += align256(T * sizeof(int));
+    L.tok_end = off;   off += align256(T * sizeof(int));
+    if (pass != TTT_PASS_FWD) {
+        const size_t kv = T * (size_t)p->hkv * (size_t)p->head_dim * sizeof(float);
+        L.delta = off; off += align256((size_t)p->k * p->hq * T * sizeof(float));
+        L.dk0 = off;   off += align256(kv);
+        L.dv0 = off;   off += align256(kv);
+        if (pass == TTT_PASS_BWD_ACCUM) {
+            L.dkl = off; off += align256(kv * (size_t)(p->k - 1));
+            L.dvl = off; off += align256(kv * (size_t)(p->k - 1));
+        }
+    }
+    L.total = off > 0 ? off : 256;
+    return L;
+}
+
+void fill_geometry(ttt::Geometry& g, const ttt_attn_params* p) {
+    g.T = p->total_tokens;
+    g.k = p->k;
+    g.step_begin = p->step_begin;
+    g.n_steps = p->step_end - p->step_begin;
+    g.hq = p->hq;
+    g.hkv = p->hkv;
+    g.G = p->hq / p->hkv;
+    g.scale = p->softmax_scale;
+    g.scale_log2 = p->softmax_scale * 1.44269504088896340736f;
+    g.q_st = p->q_stride_token;
+    g.q_sh = p->q_stride_head;
+    g.kv_st = p->kv_stride_token;
+    g.kv_sh = p->kv_stride_head;
+}
+
+int check_workspace(const void* ws, size_t have, size_t need) {
+    if (!ws) return fail(TTT_ERR_WORKSPACE, "workspace is NULL (need %zu bytes)", need);
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return fail(TTT_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+    if (have < need) return fail(TTT_ERR_WORKSPACE, "workspace has %zu bytes, need %zu", have, need);
+    return TTT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ttt_attn_last_error(void) { return g_err; }
+
+size_t ttt_attn_workspace_bytes(const ttt_attn_params* params, int pass) {
+    if (check_params(params) != TTT_OK) return 0;
+    if (pass != TTT_PASS_FWD && pass != TTT_PASS_BWD && pass != TTT_PASS_BWD_ACCUM) {
+        fail(TTT_ERR_INVALID_ARG, "pass %d is not one of TTT_PASS_*", pass);
+        return 0;
+    }
+    return make_layout(params, pass).total;
+}
+
+int ttt_attn_fwd(const ttt_attn_params* p, const void* const* q, const void* const* k, const void* const* v,
+                 const int32_t* cu_dev, const int32_t* cu_host, void* const* o, float* const* lse, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+    int rc = check_params(p);
+    if (rc != TTT_OK) return rc;
+    if (!q || !k || !v || !o || !lse) return fail(TTT_ERR_INVALID_ARG, "a step-pointer array is NULL");
+    rc = check_cu(p, cu_dev, cu_host);
+    if (rc != TTT_OK) return rc;
+    if (p->total_tokens == 0 || p->step_begin == p->step_end) return TTT_OK;
+    for (int j = p->step_begin; j < p->step_end; ++j) {
+        if ((rc = check_ptr(q[j], "q", j)) != TTT_OK) return rc;
+        if ((rc = check_ptr(o[j], "o", j)) != TTT_OK) return rc;
+        if ((rc = check_ptr(lse[j], "lse", j)) != TTT_OK) return rc;
+    }
+    for (int l = 0; l < p->step_end; ++l) {
+        if ((rc = check_ptr(k[l], "k", l)) != TTT_OK) return rc;
+        if ((rc = check_ptr(v[l], "v", l)) != TTT_OK) return rc;
+    }
+    const Layout L = make_layout(p, TTT_PASS_FWD);
+    if ((rc = check_workspace(workspace, workspace_bytes, L.total)) != TTT_OK) return rc;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    int* tok_start = reinterpret_cast<int*>(ws + L.tok_start);
+    int* tok_end = reinterpret_cast<int*>(ws + L.tok_end);
+    hipError_t e = ttt::launch_tok_bounds(cu_dev, p->n_docs, p->total_tokens, tok_start, tok_end, stream);
+    if (e != hipSuccess) return fail(TTT_ERR_HIP, "token-bounds kernel launch: %s", hipGetErrorString(e));
+
+    ttt::FwdArgs a;
+    std::memset(&a, 0, sizeof(a));
+    fill_geometry(a.geo, p);
+    for (int s = 0; s < p->k; ++s) {
+        a.q[s] = q[s];
+        a.k[s] = k[s];
+        a.v[s] = v[s];
+        a.o[s] = o[s];
+        a.lse[s] = lse[s];
+    }
+    a.tok_start = tok_start;
+    e = ttt::launch_fwd(p->dtype, p->head_dim, a, stream);
+    if (e != hipSuccess) return fail(TTT_ERR_HIP, "forward kernel launch: %s", hipGetErrorString(e));
+    return TTT_OK;
+}
+
+int ttt_attn_bwd(const ttt_attn_params* p, const void* const* q, const void* const* k, const void* const* v,
+                 const void* const* o, const float* const* lse, const void* const* d_o, const int32_t* cu_dev,
+                 const int32_t* cu_host, void* const* dq, void* const* dk, void* const* dv, int accumulate_dkv,
+                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+    int rc = check_params(p);
+    if (rc != TTT_OK) return rc;
+    if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv) return fail(TTT_ERR_INVALID_ARG, "a step-pointer array is NULL");
+    if (accumulate_dkv != 0 && accumulate_dkv != 1) return fail(TTT_ERR_INVALID_ARG, "accumulate_dkv must be 0 or 1");
+    rc = check_cu(p, cu_dev, cu_host);
+    if (rc != TTT_OK) return rc;
+    if (p->total_tokens == 0 || p->step_begin == p->step_end) return TTT_OK;
+    for (int j = p->step_begin; j < p->step_end; ++j) {
+        if ((rc = check_ptr(q[j], "q", j)) != TTT_OK) return rc;
+        if ((rc = check_ptr(o[j], "o", j)) != TTT_OK) return rc;
+        if ((rc = check_ptr(lse[j], "lse", j)) != TTT_OK) return rc;
+        if ((rc = check_ptr(d_o[j], "d_o", j)) != TTT_OK) return rc;
+        if ((rc = check_ptr(dq[j], "dq", j)) != TTT_OK) return rc;
+    }
+    for (int l = 0; l < p->step_end; ++l) {
+        if ((rc = check_ptr(k[l], "k", l)) != TTT_OK) return rc;
+        if ((rc = check_ptr(v[l], "v", l)) != TTT_OK) return rc;
+        // blocks written by this call: all l < step_end without carry, l in range (and block 0 at the end) with it
+        const bool written = !accumulate_dkv || l >= p->step_begin;
+        if (written) {
+            if ((rc = check_ptr(dk[l], "dk", l)) != TTT_OK) return rc;
+            if ((rc = check_ptr(dv[l], "dv", l)) != TTT_OK) return rc;
+        }
+    }
+    const int pass = accumulate_dkv ? TTT_PASS_BWD_ACCUM : TTT_PASS_BWD;
+    const Layout L = make_layout(p, pass);
+    if ((rc = check_workspace(workspace, workspace_bytes, L.total)) != TTT_OK) return rc;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    char* ws = static_cast<char*>(workspace);
+    int* tok_start = reinterpret_cast<int*>(ws + L.tok_start);
+    int* tok_end = reinterpret_cast<int*>(ws + L.tok_end);
+    hipError_t e = ttt::launch_tok_bounds(cu_dev, p->n_docs, p->total_tokens, tok_start, tok_end, stream);
+    if (e != hipSuccess) return fail(TTT_ERR_HIP, "token-bounds kernel launch: %s", hipGetErrorString(e));
+
+    ttt::BwdArgs a;
+    std::memset(&a, 0, sizeof(a));
+    fill_geometry(a.geo, p);
+    for (int s = 0; s < p->k; ++s) {
+        a.q[s] = q[s];
+        a.k[s] = k[s];
+        a.v[s] = v[s];
+        a.o[s] = o[s];
+        a.lse[s] = lse[s];
+        a.d_o[s] = d_o[s];
+        a.dq[s] = dq[s];
+        a.dk[s] = dk[s];
+        a.dv[s] = dv[s];
+    }
+    a.tok_start = tok_start;
+    a.tok_end = tok_end;
+    a.delta = reinterpret_cast<float*>(ws + L.delta);
+    a.dk0_acc = reinterpret_cast<float*>(ws + L.dk0);
+    a.dv0_acc = reinterpret_cast<float*>(ws + L.dv0);
+    a.accumulate = accumulate_dkv;
+    a.carry_reset = accumulate_dkv && p->step_end == p->k;
+    if (accumulate_dkv && p->k > 1) {
+        a.dkl_acc = reinterpret_cast<float*>(ws + L.dkl);
+        a.dvl_acc = reinterpret_cast<float*>(ws + L.dvl);
+    }
+    e = ttt::launch_bwd(p->dtype, p->head_dim, a, stream);
+    if (e != hipSuccess) return fail(TTT_ERR_HIP, "backward kernel launch: %s", hipGetErrorString(e));
+    return TTT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,69 @@
+// Kernel argument blocks (host fills, device reads) and the launcher prototypes that connect the
+// C-ABI file to the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ttt_device.hpp"
+
+namespace ttt {
+
+constexpr int kMaxSteps = 32;
+
+struct Geometry {
+    int T;               // packed tokens
+    int k;               // cache blocks
+    int step_begin, n_steps;
+    int hq, hkv, G;
+    float scale;         // softmax_scale
+    float scale_log2;    // softmax_scale * log2(e)
+    int64_t q_st, q_sh;  // strides (elements) of Q/O/dO/dQ
+    int64_t kv_st, kv_sh;
+};
+
+struct FwdArgs {
+    Geometry geo;
+    const void* q[kMaxSteps];
+    const void* k[kMaxSteps];
+    const void* v[kMaxSteps];
+    void* o[kMaxSteps];
+    float* lse[kMaxSteps];
+    const int* tok_start;   // [T] first token of each token's document
+    int n_tiles;            // query tiles over the packed token axis
+    HeadMap map;
+};
+
+struct BwdArgs {
+    Geometry geo;
+    const void* q[kMaxSteps];
+    const void* k[kMaxSteps];
+    const void* v[kMaxSteps];
+    const void* o[kMaxSteps];
+    const float* lse[kMaxSteps];
+    const void* d_o[kMaxSteps];
+    void* dq[kMaxSteps];
+    void* dk[kMaxSteps];
+    void* dv[kMaxSteps];
+    const int* tok_start;   // [T]
+    const int* tok_end;     // [T] one past the last token of each token's document
+    float* delta;           // [n_steps][hq][T]  D = <dO, O>
+    float* dk0_acc;         // [T][hkv][d] fp32, block-0 partial sums (atomics)
+    float* dv0_acc;
+    float* dkl_acc;         // [k-1][T][hkv][d] fp32 carry for blocks l>=1 (accumulate mode), else null
+    float* dvl_acc;
+    int accumulate;         // 0/1
+    int carry_reset;        // accumulate mode: this call starts the sweep (carry is overwritten, not read)
+    int n_tiles;            // tiles of the kernel being launched
+    int n_split;            // dK/dV kernel: ways the (step, head) list of one kv tile is split
+    HeadMap map;
+};
+
+// launchers (defined in the kernel files); all enqueue on `stream` and return the launch status
+hipError_t launch_tok_bounds(const int* cu_dev, int n_docs, int T, int* tok_start, int* tok_end, hipStream_t stream);
+hipError_t launch_fwd(int dtype, int head_dim, FwdArgs& a, hipStream_t stream);
+hipError_t launch_bwd(int dtype, int head_dim, BwdArgs& a, hipStream_t stream);
+
+// tile heights the host needs for grid sizes
+int fwd_q_tile(int dtype, int head_dim);
+
+}  // namespace ttt

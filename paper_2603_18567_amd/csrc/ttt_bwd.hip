@@ -1,0 +1,622 @@
+// Backward TTT attention kernels (gfx950).  Nothing but O and LSE was kept by the forward
+// (Sec. 4.2.1), so every kernel here recomputes p = exp(s - LSE) from Q and K tile by tile and
+// applies the softmax-attention VJP:  D = <dO,O>, dp = <dO,V>, ds = p (dp - D).
+//
+//   ttt_bwd_pre_kernel   D for every (step, head, token); and the complete dK_l, dV_l of the later
+//                        cache blocks l >= 1, which are only ever read on the diagonal (suffix part
+//                        of Alg. 2), so one small group of lanes owns each (token, kv head) -- no atomics.
+//   ttt_bwd_dq_kernel    query-stationary, same streaming structure as the forward: dQ_j.
+//   ttt_bwd_dkv_kernel   key-stationary over block 0: each wave keeps 32 rows of K_0, V_0 as
+//                        operands and their dK, dV accumulators in registers while every
+//                        (step, head of the group, query tile at or below the diagonal) streams past
+//                        through LDS; partial sums of the (step, head) splits meet in fp32 atomics.
+//   ttt_bwd_finish_kernel  fp32 block-0 sums -> dK_0, dV_0 in the tensor dtype.
+#include "ttt_args.hpp"
+
+namespace ttt {
+
+constexpr float kLog2e = 1.44269504088896340736f;
+
+// ------------------------------------------------------------------------------------------------
+// D and the diagonal blocks' dK_l, dV_l
+// ------------------------------------------------------------------------------------------------
+template <int LPR> TTT_DEV float group_sum(float v) {
+#pragma unroll
+    for (int s = 1; s < LPR; s <<= 1) v += __shfl_xor(v, s, 64);
+    return v;
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void ttt_bwd_pre_kernel(const BwdArgs a) {
+    using frag = typename Elem<T>::frag;
+    constexpr int LPR = D / 8;       // lanes that share one (token, kv head): 8 elements each
+    constexpr int UPB = 256 / LPR;   // (token, kv head) units per workgroup
+    extern __shared__ float sD[];    // [UPB][n_steps*G]
+
+    const Geometry& geo = a.geo;
+    const int Tn = geo.T, G = geo.G, ns = geo.n_steps, b = geo.step_begin, e = b + ns;
+    const int grp = threadIdx.x / LPR, sub = threadIdx.x % LPR;
+    const int64_t unit = (int64_t)blockIdx.x * UPB + grp;
+    const bool valid = unit < (int64_t)Tn * geo.hkv;
+    const int i = valid ? (int)(unit / geo.hkv) : 0;
+    const int g = valid ? (int)(unit % geo.hkv) : 0;
+    float* myD = sD + grp * (ns * G);
+
+    // phase 1: D_j[h,i] = <dO_j[i,h], O_j[i,h]>
+    for (int js = 0; js < ns; ++js) {
+        const int j = b + js;
+        for (int hg = 0; hg < G; ++hg) {
+            const int h = g * G + hg;
+            const int64_t off = (int64_t)i * geo.q_st + (int64_t)h * geo.q_sh + sub * 8;
+            const frag go = gload_frag<T>(static_cast<const T*>(a.d_o[j]) + off);
+            const frag oo = gload_frag<T>(static_cast<const T*>(a.o[j]) + off);
+            float d = 0.f;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) d = fmaf(to_f32<T>(go[x]), to_f32<T>(oo[x]), d);
+            d = group_sum<LPR>(d);
+            if (sub == 0) {
+                myD[js * G + hg] = d;
+                if (valid) a.delta[((int64_t)js * geo.hq + h) * Tn + i] = d;
+            }
+        }
+    }
+    __syncthreads();
+    if (!valid) return;
+
+    // phase 2: blocks l >= 1 see only the queries at their own token, steps j >= l
+    for (int lb = 1; lb < e; ++lb) {
+        const int64_t kvoff = (int64_t)i * geo.kv_st + (int64_t)g * geo.kv_sh + sub * 8;
+        const frag kf = gload_frag<T>(static_cast<const T*>(a.k[lb]) + kvoff);
+        const frag vf = gload_frag<T>(static_cast<const T*>(a.v[lb]) + kvoff);
+        float dk[8], dv[8];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) dk[x] = dv[x] = 0.f;
+        for (int j = (lb > b ? lb : b); j < e; ++j) {
+            for (int hg = 0; hg < G; ++hg) {
+                const int h = g * G + hg;
+                const int64_t off = (int64_t)i * geo.q_st + (int64_t)h * geo.q_sh + sub * 8;
+                const frag qf = gload_frag<T>(static_cast<const T*>(a.q[j]) + off);
+                const frag go = gload_frag<T>(static_cast<const T*>(a.d_o[j]) + off);
+                float s = 0.f, dp = 0.f;
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    s = fmaf(to_f32<T>(qf[x]), to_f32<T>(kf[x]), s);
+                    dp = fmaf(to_f32<T>(go[x]), to_f32<T>(vf[x]), dp);
+                }
+                s = group_sum<LPR>(s);
+                dp = group_sum<LPR>(dp);
+                const float lse = a.lse[j][(int64_t)h * Tn + i];
+                const float p = fast_exp2((s * geo.scale - lse) * kLog2e);
+                const float ds = p * (dp - myD[(j - b) * G + hg]) * geo.scale;
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    dk[x] = fmaf(ds, to_f32<T>(qf[x]), dk[x]);
+                    dv[x] = fmaf(p, to_f32<T>(go[x]), dv[x]);
+                }
+            }
+        }
+        if (a.accumulate) {
+            // fp32 carry across the calls of a descending-step sweep; this group owns its slice
+            const int64_t coff = (((int64_t)(lb - 1) * Tn + i) * geo.hkv + g) * D + sub * 8;
+            float* ck = a.dkl_acc + coff;
+            float* cv = a.dvl_acc + coff;
+            if (!a.carry_reset) {
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    dk[x] += ck[x];
+                    dv[x] += cv[x];
+                }
+            }
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                ck[x] = dk[x];
+                cv[x] = dv[x];
+            }
+            if (lb < b) continue;   // not complete yet: earlier steps' calls have not run
+        }
+        T* gk = static_cast<T*>(a.dk[lb]) + kvoff;
+        T* gv = static_cast<T*>(a.dv[lb]) + kvoff;
+        gstore_vec4<T>(gk, dk[0], dk[1], dk[2], dk[3]);
+        gstore_vec4<T>(gk + 4, dk[4], dk[5], dk[6], dk[7]);
+        gstore_vec4<T>(gv, dv[0], dv[1], dv[2], dv[3]);
+        gstore_vec4<T>(gv + 4, dv[4], dv[5], dv[6], dv[7]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dQ: query-stationary
+// ------------------------------------------------------------------------------------------------
+template <typename T, int D, int QB, int NW>
+__global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_kernel(const BwdArgs a) {
+    using E = Elem<T>;
+    using frag = typename E::frag;
+    constexpr int KT = 64;
+    constexpr int KB = KT / 32;
+    constexpr int QT = NW * QB * 32;
+    constexpr int DC = D / 16;
+    constexpr int DB = D / 32;
+    constexpr int NT = NW * 64;
+    constexpr int TILE_BYTES = KT * D * E::kBytes;
+
+    extern __shared__ __align__(16) char smem[];
+    auto sK = [&](int s) -> char* { return smem + s * TILE_BYTES; };
+    auto sV = [&](int s) -> char* { return smem + (2 + s) * TILE_BYTES; };
+
+    const Geometry& geo = a.geo;
+    int g, rest;
+    if (!decode_block(a.map, blockIdx.x, g, rest)) return;
+    const int hg = rest % geo.G;
+    rest /= geo.G;
+    const int js = rest % geo.n_steps;
+    const int j = geo.step_begin + js;
+    const int tile = a.n_tiles - 1 - rest / geo.n_steps;
+    const int h = g * geo.G + hg;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, hh = lane >> 5;
+    const int Tn = geo.T;
+    const int q_tile0 = tile * QT;
+    const int wq0 = q_tile0 + wave * (QB * 32);
+    const bool active = wq0 < Tn;
+
+    const T* Qj = static_cast<const T*>(a.q[j]) + (int64_t)h * geo.q_sh;
+    const T* dOj = static_cast<const T*>(a.d_o[j]) + (int64_t)h * geo.q_sh;
+    const T* K0 = static_cast<const T*>(a.k[0]) + (int64_t)g * geo.kv_sh;
+    const T* V0 = static_cast<const T*>(a.v[0]) + (int64_t)g * geo.kv_sh;
+
+    int qi[QB], qc[QB], st[QB];
+    float lse2[QB], dl[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        qi[qb] = wq0 + 32 * qb + n;
+        qc[qb] = qi[qb] < Tn ? qi[qb] : Tn - 1;
+        st[qb] = a.tok_start[qc[qb]];
+        lse2[qb] = a.lse[j][(int64_t)h * Tn + qc[qb]] * kLog2e;
+        dl[qb] = a.delta[((int64_t)js * geo.hq + h) * Tn + qc[qb]];
+    }
+    const int hi_w = min(wq0 + QB * 32 - 1, Tn - 1);
+    const int lo_w = active ? __builtin_amdgcn_readfirstlane(a.tok_start[min(wq0, Tn - 1)]) : 0;
+    const int st_hi = active ? __builtin_amdgcn_readfirstlane(a.tok_start[hi_w]) : 0;
+    const int lo = __builtin_amdgcn_readfirstlane(a.tok_start[q_tile0]);
+    const int hi = min(q_tile0 + QT - 1, Tn - 1);
+    const int u_lo = lo / KT, u_hi = hi / KT;
+
+    frag qf[QB][DC], gof[QB][DC];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int t = 0; t < DC; ++t) {
+            qf[qb][t] = gload_frag<T>(Qj + (int64_t)qc[qb] * geo.q_st + t * 16 + hh * 8);
+            gof[qb][t] = gload_frag<T>(dOj + (int64_t)qc[qb] * geo.q_st + t * 16 + hh * 8);
+        }
+
+    f32x16 dqacc[QB][DB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dqacc[qb][db][i] = 0.f;
+    const float c = geo.scale_log2;
+
+    tile_load_async<T, D, KT, NT>(sK(0), K0, geo.kv_st, u_lo * KT, Tn - 1, tid);
+    tile_load_async<T, D, KT, NT>(sV(0), V0, geo.kv_st, u_lo * KT, Tn - 1, tid);
+    int stage = 0;
+    for (int u = u_lo; u <= u_hi; ++u) {
+        wait_async_copies();
+        __syncthreads();
+        if (u < u_hi) {
+            tile_load_async<T, D, KT, NT>(sK(stage ^ 1), K0, geo.kv_st, (u + 1) * KT, Tn - 1, tid);
+            tile_load_async<T, D, KT, NT>(sV(stage ^ 1), V0, geo.kv_st, (u + 1) * KT, Tn - 1, tid);
+        }
+        const int kv0 = u * KT;
+        if (active && kv0 <= hi_w && kv0 + KT - 1 >= lo_w) {
+            const char* tk = sK(stage);
+            const char* tv = sV(stage);
+            f32x16 sacc[KB][QB], pacc[KB][QB];
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sacc[kb][qb][i] = pacc[kb][qb][i] = 0.f;
+            // S^T = K Q^T and dP^T = V dO^T
+#pragma unroll
+            for (int t = 0; t < DC; ++t) {
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) {
+                    const frag kf = frag_rowwise<T, D>(tk, kb * 32 + n, t * 16 + hh * 8);
+                    const frag vf = frag_rowwise<T, D>(tv, kb * 32 + n, t * 16 + hh * 8);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) {
+                        sacc[kb][qb] = mma(kf, qf[qb][t], sacc[kb][qb]);
+                        pacc[kb][qb] = mma(vf, gof[qb][t], pacc[kb][qb]);
+                    }
+                }
+            }
+            const bool need_mask = kv0 + KT - 1 > wq0 || kv0 < st_hi;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        float p = fast_exp2(fmaf(sacc[kb][qb][i], c, -lse2[qb]));
+                        if (need_mask) {
+                            const int kv = kv0 + kb * 32 + acc_row(i, hh);
+                            p = (kv <= qi[qb] && kv >= st[qb]) ? p : 0.f;
+                        }
+                        sacc[kb][qb][i] = p * (pacc[kb][qb][i] - dl[qb]);   // dS^T
+                    }
+            // dQ^T[d, q] += K^T dS^T
+#pragma unroll
+            for (int c4 = 0; c4 < KT / 16; ++c4) {
+                frag sf[QB];
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) sf[qb] = acc_chunk<T>(sacc[c4 / 2][qb], c4 % 2);
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const frag kt = frag_transposed<T, D>(tk, c4 * 16, db * 32, lane);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) dqacc[qb][db] = mma(kt, sf[qb], dqacc[qb][db]);
+                }
+            }
+        }
+        stage ^= 1;
+    }
+    if (!active) return;
+
+    // diagonal keys of blocks 1..j
+    for (int lb = 1; lb <= j; ++lb) {
+        const T* Kl = static_cast<const T*>(a.k[lb]) + (int64_t)g * geo.kv_sh;
+        const T* Vl = static_cast<const T*>(a.v[lb]) + (int64_t)g * geo.kv_sh;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const T* krow = Kl + (int64_t)qc[qb] * geo.kv_st;
+            const T* vrow = Vl + (int64_t)qc[qb] * geo.kv_st;
+            float s = 0.f, dp = 0.f;
+#pragma unroll
+            for (int t = 0; t < DC; ++t) {
+                const frag kf = gload_frag<T>(krow + t * 16 + hh * 8);
+                const frag vf = gload_frag<T>(vrow + t * 16 + hh * 8);
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    s = fmaf(to_f32<T>(qf[qb][t][x]), to_f32<T>(kf[x]), s);
+                    dp = fmaf(to_f32<T>(gof[qb][t][x]), to_f32<T>(vf[x]), dp);
+                }
+            }
+            s += xor32(s);
+            dp += xor32(dp);
+            const float p = fast_exp2(fmaf(s, c, -lse2[qb]));
+            const float ds = p * (dp - dl[qb]);
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const typename E::vec4 kk = gload_vec4<T>(krow + db * 32 + i4 * 8 + hh * 4);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        dqacc[qb][db][i4 * 4 + x] = fmaf(ds, to_f32<T>(kk[x]), dqacc[qb][db][i4 * 4 + x]);
+                }
+        }
+    }
+
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        if (qi[qb] < Tn) {
+            T* row = static_cast<T*>(a.dq[j]) + (int64_t)h * geo.q_sh + (int64_t)qi[qb] * geo.q_st;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4)
+                    gstore_vec4<T>(row + db * 32 + i4 * 8 + hh * 4, dqacc[qb][db][i4 * 4 + 0] * geo.scale,
+                                   dqacc[qb][db][i4 * 4 + 1] * geo.scale, dqacc[qb][db][i4 * 4 + 2] * geo.scale,
+                                   dqacc[qb][db][i4 * 4 + 3] * geo.scale);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dK_0, dV_0: key-stationary
+// ------------------------------------------------------------------------------------------------
+template <typename T, int D, int NW>
+__global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_kernel(const BwdArgs a) {
+    using E = Elem<T>;
+    using frag = typename E::frag;
+    constexpr int KVT = NW * 32;   // kv rows per workgroup, 32 per wave
+    constexpr int QTL = 64;        // query rows per LDS tile
+    constexpr int DC = D / 16;
+    constexpr int DB = D / 32;
+    constexpr int NT = NW * 64;
+    constexpr int TILE_BYTES = QTL * D * E::kBytes;
+    constexpr int ROWV_BYTES = QTL * 4;
+    constexpr int STAGE_BYTES = 2 * TILE_BYTES + 3 * ROWV_BYTES;
+
+    extern __shared__ __align__(16) char smem[];
+    auto sQ = [&](int s) -> char* { return smem + s * STAGE_BYTES; };
+    auto sG = [&](int s) -> char* { return smem + s * STAGE_BYTES + TILE_BYTES; };
+    auto sLse = [&](int s) -> float* { return reinterpret_cast<float*>(smem + s * STAGE_BYTES + 2 * TILE_BYTES); };
+    auto sDl = [&](int s) -> float* { return sLse(s) + QTL; };
+    auto sSt = [&](int s) -> int* { return reinterpret_cast<int*>(sLse(s) + 2 * QTL); };
+
+    const Geometry& geo = a.geo;
+    int g, rest;
+    if (!decode_block(a.map, blockIdx.x, g, rest)) return;
+    const int sp = rest % a.n_split;
+    const int tile = rest / a.n_split;   // low tiles of a document have the longest query range: first
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, hh = lane >> 5;
+    const int Tn = geo.T;
+    const int kv_tile0 = tile * KVT;
+    const int wk0 = kv_tile0 + wave * 32;          // first kv row of this wave
+    const bool active = wk0 < Tn;
+    const int wk_hi = min(wk0 + 31, Tn - 1);
+    // query rows that can see this workgroup's / this wave's keys
+    const int q_end = __builtin_amdgcn_readfirstlane(a.tok_end[min(kv_tile0 + KVT - 1, Tn - 1)]);
+    const int wq_end = active ? __builtin_amdgcn_readfirstlane(a.tok_end[wk_hi]) : 0;
+    const int qt_lo = kv_tile0 / QTL;
+    const int qt_hi = (q_end - 1) / QTL;
+    const int nqt = qt_hi - qt_lo + 1;
+    const int n_jh = geo.n_steps * geo.G;
+    const int n_c = (n_jh - sp + a.n_split - 1) / a.n_split;   // (step, head) pairs of this split
+    const int n_it = n_c * nqt;
+
+    const T* K0 = static_cast<const T*>(a.k[0]) + (int64_t)g * geo.kv_sh;
+    const T* V0 = static_cast<const T*>(a.v[0]) + (int64_t)g * geo.kv_sh;
+    const int kc = min(wk0 + n, Tn - 1);
+    const int kvi = wk0 + n;   // this lane's kv row (accumulator column)
+    // K_0, V_0 rows as stationary B operands: lane (n,hh) holds row n, elements 16t + 8hh .. +8
+    frag kf[DC], vf[DC];
+#pragma unroll
+    for (int t = 0; t < DC; ++t) {
+        kf[t] = gload_frag<T>(K0 + (int64_t)kc * geo.kv_st + t * 16 + hh * 8);
+        vf[t] = gload_frag<T>(V0 + (int64_t)kc * geo.kv_st + t * 16 + hh * 8);
+    }
+    f32x16 dkacc[DB], dvacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dkacc[db][i] = dvacc[db][i] = 0.f;
+    const float c = geo.scale_log2;
+
+    // stage loader: query tile `qt` of (step, head) pair number `ci` of this split
+    auto issue = [&](int it, int s) {
+        const int ci = it / nqt, qt = qt_lo + it % nqt;
+        const int jh = sp + ci * a.n_split;
+        const int js = jh / geo.G, h = g * geo.G + jh % geo.G;
+        const int j = geo.step_begin + js;
+        const T* Qj = static_cast<const T*>(a.q[j]) + (int64_t)h * geo.q_sh;
+        const T* dOj = static_cast<const T*>(a.d_o[j]) + (int64_t)h * geo.q_sh;
+        tile_load_async<T, D, QTL, NT>(sQ(s), Qj, geo.q_st, qt * QTL, Tn - 1, tid);
+        tile_load_async<T, D, QTL, NT>(sG(s), dOj, geo.q_st, qt * QTL, Tn - 1, tid);
+        if (tid < QTL) {
+            const int q = qt * QTL + tid;
+            const bool in = q < Tn;
+            const int qq = in ? q : Tn - 1;
+            // rows past the end get LSE = +inf so that p = 0
+            sLse(s)[tid] = in ? a.lse[j][(int64_t)h * Tn + qq] * kLog2e : INFINITY;
+            sDl(s)[tid] = in ? a.delta[((int64_t)js * geo.hq + h) * Tn + qq] : 0.f;
+            sSt(s)[tid] = a.tok_start[qq];
+        }
+    };
+
+    if (n_it > 0) issue(0, 0);
+    int stage = 0;
+    for (int it = 0; it < n_it; ++it) {
+        wait_async_copies();
+        __syncthreads();
+        if (it + 1 < n_it) issue(it + 1, stage ^ 1);
+        const int q0 = (qt_lo + it % nqt) * QTL;
+        // this wave's keys are seen by query rows [wk0, wq_end)
+        if (active && q0 + QTL - 1 >= wk0 && q0 < wq_end) {
+            const char* tq = sQ(stage);
+            const char* tg = sG(stage);
+            const float* tl = sLse(stage);
+            const float* td = sDl(stage);
+            const int* ts = sSt(stage);
+#pragma unroll
+            for (int qb = 0; qb < QTL / 32; ++qb) {
+                const int qb0 = q0 + qb * 32;
+                if (qb0 + 31 < wk0 || qb0 >= wq_end) continue;
+                // S[q, kv] = Q K^T and dP[q, kv] = dO V^T : lane = kv column, values = query rows
+                f32x16 sacc, pacc;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[i] = pacc[i] = 0.f;
+#pragma unroll
+                for (int t = 0; t < DC; ++t) {
+                    const frag qa = frag_rowwise<T, D>(tq, qb * 32 + n, t * 16 + hh * 8);
+                    const frag ga = frag_rowwise<T, D>(tg, qb * 32 + n, t * 16 + hh * 8);
+                    sacc = mma(qa, kf[t], sacc);
+                    pacc = mma(ga, vf[t], pacc);
+                }
+                // every row of the block sees every key of the wave iff the block is below the
+                // wave's last key and starts its document at or before the wave's first key
+                const bool need_mask = qb0 < wk0 + 31 || ts[min(qb * 32 + 31, QTL - 1)] > wk0 || qb0 + 31 >= wq_end;
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const int r = qb * 32 + i4 * 8 + hh * 4;
+                    const f32x4 l4 = *reinterpret_cast<const f32x4*>(tl + r);
+                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(td + r);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        const int i = i4 * 4 + x;
+                        float p = fast_exp2(fmaf(sacc[i], c, -l4[x]));
+                        if (need_mask) {
+                            const int q = q0 + r + x;
+                            p = (kvi <= q && kvi >= ts[r + x]) ? p : 0.f;
+                        }
+                        sacc[i] = p;                       // P
+                        pacc[i] = p * (pacc[i] - d4[x]);   // dS
+                    }
+                }
+                // dV[kv, d] += P^T dO ;  dK[kv, d] += dS^T Q
+#pragma unroll
+                for (int c2 = 0; c2 < 2; ++c2) {
+                    const frag pf = acc_chunk<T>(sacc, c2);
+                    const frag sf = acc_chunk<T>(pacc, c2);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        const frag gt = frag_transposed<T, D>(tg, qb * 32 + c2 * 16, db * 32, lane);
+                        const frag qt = frag_transposed<T, D>(tq, qb * 32 + c2 * 16, db * 32, lane);
+                        dvacc[db] = mma(pf, gt, dvacc[db]);
+                        dkacc[db] = mma(sf, qt, dkacc[db]);
+                    }
+                }
+            }
+        }
+        stage ^= 1;
+    }
+    if (!active) return;
+
+    // fp32 partial sums of this split -> block-0 accumulators [T][hkv][D]
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int kv = wk0 + acc_row(i, hh);
+            if (kv < Tn) {
+                const int64_t off = ((int64_t)kv * geo.hkv + g) * D + db * 32 + n;
+                atomicAdd(a.dk0_acc + off, dkacc[db][i]);
+                atomicAdd(a.dv0_acc + off, dvacc[db][i]);
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------------------
+// small helpers: clear the block-0 accumulators; convert them to the output dtype
+// ------------------------------------------------------------------------------------------------
+__global__ void ttt_fill_zero_kernel(f32x4* __restrict__ p, int64_t n4) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) p[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+}
+
+template <typename T, int D>
+__global__ void ttt_bwd_finish_kernel(const BwdArgs a) {
+    const Geometry& geo = a.geo;
+    const int64_t n4 = (int64_t)geo.T * geo.hkv * (D / 4);
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; x < n4; x += stride) {
+        const int d4 = (int)(x % (D / 4));
+        const int64_t tg = x / (D / 4);
+        const int g = (int)(tg % geo.hkv);
+        const int64_t t = tg / geo.hkv;
+        const f32x4 k4 = reinterpret_cast<const f32x4*>(a.dk0_acc)[x];
+        const f32x4 v4 = reinterpret_cast<const f32x4*>(a.dv0_acc)[x];
+        const int64_t off = t * geo.kv_st + (int64_t)g * geo.kv_sh + d4 * 4;
+        gstore_vec4<T>(static_cast<T*>(a.dk[0]) + off, k4[0] * geo.scale, k4[1] * geo.scale, k4[2] * geo.scale,
+                       k4[3] * geo.scale);
+        gstore_vec4<T>(static_cast<T*>(a.dv[0]) + off, v4[0], v4[1], v4[2], v4[3]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// launch sequence
+// ------------------------------------------------------------------------------------------------
+static void set_head_map(HeadMap& m, int hkv, int rest_count, int64_t& grid) {
+    m.hkv = hkv;
+    m.rest_count = rest_count;
+    if (hkv % 8 == 0) {
+        m.mode = 1;
+        grid = (int64_t)hkv * rest_count;
+    } else if (8 % hkv == 0) {
+        m.mode = 2;
+        const int xp = 8 / hkv;
+        grid = 8 * (int64_t)((rest_count + xp - 1) / xp);
+    } else {
+        m.mode = 0;
+        grid = (int64_t)hkv * rest_count;
+    }
+}
+
+template <typename T, int D, int QB_DQ, int NW_DQ, int NW_KV>
+static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
+    const Geometry& geo = a.geo;
+    hipError_t e;
+    const int64_t acc_n4 = (int64_t)geo.T * geo.hkv * (D / 4);
+
+    // 1. clear the block-0 accumulators unless a carry from later steps is being continued
+    if (!a.accumulate || a.carry_reset) {
+        const int blocks = (int)((acc_n4 + 255) / 256 < 4096 ? (acc_n4 + 255) / 256 : 4096);
+        hipLaunchKernelGGL(ttt_fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<f32x4*>(a.dk0_acc), acc_n4);
+        hipLaunchKernelGGL(ttt_fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<f32x4*>(a.dv0_acc), acc_n4);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+
+    // 2. D and the diagonal blocks
+    {
+        constexpr int UPB = 256 / (D / 8);
+        const int64_t units = (int64_t)geo.T * geo.hkv;
+        const int64_t grid = (units + UPB - 1) / UPB;
+        const size_t lds = (size_t)UPB * geo.n_steps * geo.G * sizeof(float);
+        if (grid > 0x7fffffffLL || lds > 160 * 1024) return hipErrorInvalidValue;
+        auto kern = ttt_bwd_pre_kernel<T, D>;
+        if (lds > 48 * 1024) {
+            e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, stream, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+
+    // 3. dQ
+    {
+        constexpr int QT = NW_DQ * QB_DQ * 32;
+        constexpr int LDS = 4 * 64 * D * (int)sizeof(T);
+        auto kern = ttt_bwd_dq_kernel<T, D, QB_DQ, NW_DQ>;
+        static bool attr_done = false;
+        if (!attr_done) {
+            e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        a.n_tiles = (geo.T + QT - 1) / QT;
+        int64_t grid;
+        set_head_map(a.map, geo.hkv, a.n_tiles * geo.n_steps * geo.G, grid);
+        if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW_DQ * 64), LDS, stream, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+
+    // 4. dK_0, dV_0
+    {
+        constexpr int KVT = NW_KV * 32;
+        constexpr int LDS = 2 * (2 * 64 * D * (int)sizeof(T) + 3 * 64 * 4);
+        auto kern = ttt_bwd_dkv_kernel<T, D, NW_KV>;
+        static bool attr_done = false;
+        if (!attr_done) {
+            e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+            if (e != hipSuccess) return e;
+            attr_done = true;
+        }
+        a.n_tiles = (geo.T + KVT - 1) / KVT;
+        // split the (step, head) list of a kv tile so that the grid has a few thousand workgroups
+        const int n_jh = geo.n_steps * geo.G;
+        int n_split = 1;
+        while (n_split < n_jh && (int64_t)a.n_tiles * geo.hkv * n_split < 2048) ++n_split;
+        a.n_split = n_split;
+        int64_t grid;
+        set_head_map(a.map, geo.hkv, a.n_tiles * n_split, grid);
+        if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW_KV * 64), LDS, stream, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+
+    // 5. block-0 sums -> output dtype, once the sweep has covered step 0
+    if (!a.accumulate || geo.step_begin == 0) {
+        const int blocks = (int)((acc_n4 + 255) / 256 < 4096 ? (acc_n4 + 255) / 256 : 4096);
+        hipLaunchKernelGGL((ttt_bwd_finish_kernel<T, D>), dim3(blocks), dim3(256), 0, stream, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_bwd(int dtype, int head_dim, BwdArgs& a, hipStream_t stream) {
+    if (dtype == 1 && head_dim == 128) return launch_bwd_t<__bf16, 128, 1, 4, 4>(a, stream);
+    if (dtype == 1 && head_dim == 64) return launch_bwd_t<__bf16, 64, 1, 4, 4>(a, stream);
+    if (dtype == 0 && head_dim == 128) return launch_bwd_t<float, 128, 1, 4, 4>(a, stream);
+    if (dtype == 0 && head_dim == 64) return launch_bwd_t<float, 64, 1, 4, 4>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace ttt

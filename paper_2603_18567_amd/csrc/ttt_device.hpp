@@ -1,0 +1,233 @@
+// Device-side building blocks shared by the TTT attention kernels (gfx950 only).
+//
+// One matrix "atom" is a 32x32 fp32 accumulator block updated by a contraction chunk of 16:
+//   bf16:  one v_mfma_f32_32x32x16_bf16            (lane holds 8 consecutive k of its row/column)
+//   fp32:  eight v_mfma_f32_32x32x2_f32            (lane holds 8 values; MFMA u contracts value u of
+//                                                   both lane halves, i.e. k = u and k = 8+u)
+// so for both element types an operand fragment is "8 values per lane, k = 8*(lane/32) + e" and the
+// accumulator layout is the 32x32 one: lane (n = lane%32, hh = lane/32) holds column n and rows
+// row(i) = 8*(i/4) + 4*hh + i%4, i = 0..15.
+//
+// An accumulator block is turned into an operand whose contraction index is the accumulator's ROW
+// index without any data movement: the 16 values of a lane are split into two chunks of 8
+// (chunk c = values 8c..8c+7 = rows 16c + {0..3, 8..11} + 4*hh), and the other operand is read
+// "transposed" with exactly that row set per lane (frag_transposed below).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ttt {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+#define TTT_DEV __device__ __forceinline__
+
+template <typename T> struct Elem;
+template <> struct Elem<__bf16> {
+    using frag = bf16x8;
+    using vec4 = bf16x4;
+    static constexpr int kBytes = 2;
+};
+template <> struct Elem<float> {
+    using frag = f32x8;
+    using vec4 = f32x4;
+    static constexpr int kBytes = 4;
+};
+
+// ---- accumulate one contraction chunk of 16 into a 32x32 block
+TTT_DEV f32x16 mma(const bf16x8& a, const bf16x8& b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+TTT_DEV f32x16 mma(const f32x8& a, const f32x8& b, f32x16 c) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], c, 0, 0, 0);
+    return c;
+}
+
+// ---- accumulator chunk -> operand fragment (values 8c..8c+7 of the lane)
+template <typename T> TTT_DEV typename Elem<T>::frag acc_chunk(const f32x16& acc, int c);
+template <> TTT_DEV bf16x8 acc_chunk<__bf16>(const f32x16& acc, int c) {
+    bf16x8 r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = (__bf16)acc[8 * c + e];
+    return r;
+}
+template <> TTT_DEV f32x8 acc_chunk<float>(const f32x16& acc, int c) {
+    f32x8 r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = acc[8 * c + e];
+    return r;
+}
+
+// row of accumulator value i for lane half hh
+TTT_DEV constexpr int acc_row(int i, int hh) { return 8 * (i / 4) + 4 * hh + (i % 4); }
+
+// ---- LDS tiles: ROWS x D elements, row-major, each row cut into 16-byte pieces; piece c of row r
+// lives at piece position c ^ swz(r) so that both the row-wise 16-byte reads and the transposing
+// reads spread over the banks.
+template <typename T, int D> struct Tile {
+    static constexpr int kRowBytes = D * Elem<T>::kBytes;
+    static constexpr int kPieces = kRowBytes / 16;              // 8, 16 or 32
+    static constexpr int kElemsPerPiece = 16 / Elem<T>::kBytes;
+    static constexpr int kSwzMask = (kPieces < 16 ? kPieces : 16) - 1;
+    TTT_DEV static int swz(int r) { return r & kSwzMask; }
+    // byte offset of element (r, col) inside the tile
+    TTT_DEV static int offset(int r, int col) {
+        const int piece = col / kElemsPerPiece;
+        const int within = col % kElemsPerPiece;
+        return r * kRowBytes + ((piece ^ swz(r)) * 16) + within * Elem<T>::kBytes;
+    }
+};
+
+// 8 consecutive elements (r, col..col+7), col a multiple of 8: the k-contiguous operand fragment.
+template <typename T, int D> TTT_DEV typename Elem<T>::frag frag_rowwise(const char* tile, int r, int col);
+template <> TTT_DEV bf16x8 frag_rowwise<__bf16, 128>(const char* tile, int r, int col) {
+    return *reinterpret_cast<const bf16x8*>(tile + Tile<__bf16, 128>::offset(r, col));
+}
+template <> TTT_DEV bf16x8 frag_rowwise<__bf16, 64>(const char* tile, int r, int col) {
+    return *reinterpret_cast<const bf16x8*>(tile + Tile<__bf16, 64>::offset(r, col));
+}
+template <> TTT_DEV f32x8 frag_rowwise<float, 128>(const char* tile, int r, int col) {
+    const f32x4 lo = *reinterpret_cast<const f32x4*>(tile + Tile<float, 128>::offset(r, col));
+    const f32x4 hi = *reinterpret_cast<const f32x4*>(tile + Tile<float, 128>::offset(r, col + 4));
+    return f32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+}
+template <> TTT_DEV f32x8 frag_rowwise<float, 64>(const char* tile, int r, int col) {
+    const f32x4 lo = *reinterpret_cast<const f32x4*>(tile + Tile<float, 64>::offset(r, col));
+    const f32x4 hi = *reinterpret_cast<const f32x4*>(tile + Tile<float, 64>::offset(r, col + 4));
+    return f32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+}
+
+// Transposed fragment for the 32-column block starting at col0: the lane's column is col0 + lane%32
+// and its 8 values are rows row0 + {0,1,2,3, 8,9,10,11} + 4*(lane/32)  (row0 a multiple of 16).
+// bf16 uses the gfx950 transposing LDS read: inside each group of 16 lanes, lane t supplies the
+// address of 4 consecutive elements (row t/4, columns 4*(t%4)..+3 of the group's 16 columns) and
+// receives the 4 rows of column t.
+template <typename T, int D> TTT_DEV typename Elem<T>::frag frag_transposed(const char* tile, int row0, int col0, int lane);
+template <int D> TTT_DEV bf16x8 frag_transposed_bf16(const char* tile, int row0, int col0, int lane) {
+    const int t = lane & 15, grp = (lane >> 4) & 1, hh = lane >> 5;
+    const int r = row0 + 4 * hh + (t >> 2);
+    const int c = col0 + 16 * grp + 4 * (t & 3);
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_s16x4*)(uintptr_t)(tile + Tile<__bf16, D>::offset(r, c)));
+    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (lds_s16x4*)(uintptr_t)(tile + Tile<__bf16, D>::offset(r + 8, c)));
+    union { s16x4 s[2]; bf16x8 v; } u;
+    u.s[0] = a;
+    u.s[1] = b;
+    return u.v;
+}
+template <> TTT_DEV bf16x8 frag_transposed<__bf16, 128>(const char* tile, int row0, int col0, int lane) {
+    return frag_transposed_bf16<128>(tile, row0, col0, lane);
+}
+template <> TTT_DEV bf16x8 frag_transposed<__bf16, 64>(const char* tile, int row0, int col0, int lane) {
+    return frag_transposed_bf16<64>(tile, row0, col0, lane);
+}
+template <int D> TTT_DEV f32x8 frag_transposed_f32(const char* tile, int row0, int col0, int lane) {
+    const int n = lane & 31, hh = lane >> 5;
+    f32x8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int r = row0 + 8 * (e / 4) + 4 * hh + (e % 4);
+        v[e] = *reinterpret_cast<const float*>(tile + Tile<float, D>::offset(r, col0 + n));
+    }
+    return v;
+}
+template <> TTT_DEV f32x8 frag_transposed<float, 128>(const char* tile, int row0, int col0, int lane) {
+    return frag_transposed_f32<128>(tile, row0, col0, lane);
+}
+template <> TTT_DEV f32x8 frag_transposed<float, 64>(const char* tile, int row0, int col0, int lane) {
+    return frag_transposed_f32<64>(tile, row0, col0, lane);
+}
+
+// ---- global -> LDS tile copy without passing through registers (16 bytes per lane per
+// instruction; one wave instruction fills 1024 contiguous LDS bytes).  ROWS*kRowBytes must be a
+// multiple of NTHREADS*16.  Rows are clamped to [0, max_row] so the copy never leaves the tensor;
+// clamped rows are hidden by the mask later.  `g` points at element (token 0, this head, 0).
+template <typename T, int D, int ROWS, int NTHREADS>
+TTT_DEV void tile_load_async(char* tile, const T* g, int64_t stride_token, int row_first, int max_row, int tid) {
+    using TL = Tile<T, D>;
+    constexpr int kTotalPieces = ROWS * TL::kPieces;
+    static_assert(kTotalPieces % NTHREADS == 0, "tile does not divide over the workgroup");
+    constexpr int kIters = kTotalPieces / NTHREADS;
+    const int wave = tid >> 6, lane = tid & 63;
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const int base = (it * (NTHREADS / 64) + wave) * 64;   // first piece of this wave instruction
+        const int p = base + lane;
+        const int r = p / TL::kPieces;
+        const int pos = p % TL::kPieces;
+        const int piece = pos ^ TL::swz(r);
+        int gr = row_first + r;
+        gr = gr > max_row ? max_row : gr;
+        const T* src = g + (int64_t)gr * stride_token + piece * TL::kElemsPerPiece;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(uintptr_t)(tile + base * 16),
+                                         16, 0, 0);
+    }
+}
+
+// all outstanding global->LDS copies of this wave have landed
+TTT_DEV void wait_async_copies() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+
+// ---- small helpers
+TTT_DEV float xor32(float v) { return __shfl_xor(v, 32, 64); }
+TTT_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <typename T> TTT_DEV float to_f32(T v);
+template <> TTT_DEV float to_f32<float>(float v) { return v; }
+template <> TTT_DEV float to_f32<__bf16>(__bf16 v) { return (float)v; }
+
+// load 8 consecutive elements from global as a fragment
+template <typename T> TTT_DEV typename Elem<T>::frag gload_frag(const T* p);
+template <> TTT_DEV bf16x8 gload_frag<__bf16>(const __bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+template <> TTT_DEV f32x8 gload_frag<float>(const float* p) {
+    const f32x4 lo = *reinterpret_cast<const f32x4*>(p);
+    const f32x4 hi = *reinterpret_cast<const f32x4*>(p + 4);
+    return f32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+}
+template <typename T> TTT_DEV typename Elem<T>::vec4 gload_vec4(const T* p) {
+    return *reinterpret_cast<const typename Elem<T>::vec4*>(p);
+}
+template <typename T> TTT_DEV void gstore_vec4(T* p, float a, float b, float c, float d);
+template <> TTT_DEV void gstore_vec4<float>(float* p, float a, float b, float c, float d) {
+    *reinterpret_cast<f32x4*>(p) = f32x4{a, b, c, d};
+}
+template <> TTT_DEV void gstore_vec4<__bf16>(__bf16* p, float a, float b, float c, float d) {
+    *reinterpret_cast<bf16x4*>(p) = bf16x4{(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+}
+
+// Workgroup index -> (kv head, remaining index) so that workgroups that share one kv head's K_0/V_0
+// land on the same XCD (consecutive workgroup ids go round-robin over the 8 XCDs, each with its own
+// L2).  `rest_count` items per kv head; returns false for padding workgroups.
+struct HeadMap {
+    int mode;        // 0: no remap, 1: hkv multiple of 8, 2: hkv divides 8
+    int hkv;
+    int rest_count;
+};
+TTT_DEV bool decode_block(const HeadMap& m, int id, int& g, int& rest) {
+    if (m.mode == 1) {
+        const int hp = m.hkv >> 3;
+        const int xcd = id & 7, slot = id >> 3;
+        g = xcd * hp + slot % hp;
+        rest = slot / hp;
+    } else if (m.mode == 2) {
+        const int xp = 8 / m.hkv;
+        const int xcd = id & 7, slot = id >> 3;
+        g = xcd / xp;
+        rest = slot * xp + xcd % xp;
+    } else {
+        g = id % m.hkv;
+        rest = id / m.hkv;
+    }
+    return rest < m.rest_count;
+}
+
+}  // namespace ttt

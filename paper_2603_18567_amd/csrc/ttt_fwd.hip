@@ -1,0 +1,313 @@
+// Forward TTT attention kernel (gfx950): streams K_0/V_0 tiles through LDS with an online softmax
+// (Sec. 4.2.1: nothing of size T x T is stored), then folds in the <= j diagonal keys of the later
+// cache blocks (suffix part of Alg. 2) row by row on the vector ALU.
+//
+// Work split: one workgroup = one tile of QT consecutive packed tokens x one query head x one step.
+// Each wave owns QB blocks of 32 query rows and keeps, per lane, everything that belongs to ONE
+// query row: scores are computed transposed (S^T = K Q^T) so that the accumulator's column index --
+// the lane -- is the query row; running max / sum / rescale are then per-lane scalars and the only
+// cross-lane traffic of the softmax is one exchange between the two lane halves.  The same layout
+// lets exp(S^T) be fed straight back as the B operand of O^T = V^T P^T.
+//
+// Tiles are cut over the packed token axis, not per document: a row's visible prefix is
+// [tok_start[i], i], so a wave visits the kv tiles that intersect [tok_start[first row], last row]
+// and nothing else; tiles strictly inside that range for every row skip the mask code.
+#include "ttt_args.hpp"
+
+namespace ttt {
+
+template <typename T, int D, int QB, int NW>
+__global__ __launch_bounds__(NW * 64) void ttt_fwd_kernel(const FwdArgs a) {
+    using E = Elem<T>;
+    using frag = typename E::frag;
+    constexpr int KT = 64;                // kv rows per LDS tile
+    constexpr int KB = KT / 32;
+    constexpr int QT = NW * QB * 32;
+    constexpr int DC = D / 16;            // contraction chunks over head_dim
+    constexpr int DB = D / 32;            // 32-wide blocks of head_dim
+    constexpr int NT = NW * 64;
+    constexpr int TILE_BYTES = KT * D * E::kBytes;
+    constexpr float kLazy = 8.f;          // log2 of the largest p tolerated before the reference max moves
+
+    extern __shared__ __align__(16) char smem[];
+    // LDS: K stage 0, K stage 1, V stage 0, V stage 1
+    auto sK = [&](int s) -> char* { return smem + s * TILE_BYTES; };
+    auto sV = [&](int s) -> char* { return smem + (2 + s) * TILE_BYTES; };
+
+    const Geometry& geo = a.geo;
+    int g, rest;
+    if (!decode_block(a.map, blockIdx.x, g, rest)) return;
+    const int hg = rest % geo.G;
+    rest /= geo.G;
+    const int j = geo.step_begin + rest % geo.n_steps;
+    const int tile = a.n_tiles - 1 - rest / geo.n_steps;   // long-prefix tiles first
+    const int h = g * geo.G + hg;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, hh = lane >> 5;
+    const int Tn = geo.T;   // packed tokens
+    const int q_tile0 = tile * QT;
+    const int wq0 = q_tile0 + wave * (QB * 32);
+    const bool active = wq0 < Tn;
+
+    const T* Qj = static_cast<const T*>(a.q[j]) + (int64_t)h * geo.q_sh;
+    const T* K0 = static_cast<const T*>(a.k[0]) + (int64_t)g * geo.kv_sh;
+    const T* V0 = static_cast<const T*>(a.v[0]) + (int64_t)g * geo.kv_sh;
+
+    // rows of this lane, their clamped copies and document starts
+    int qi[QB], qc[QB], st[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        qi[qb] = wq0 + 32 * qb + n;
+        qc[qb] = qi[qb] < Tn ? qi[qb] : Tn - 1;
+        st[qb] = a.tok_start[qc[qb]];
+    }
+    const int hi_w = min(wq0 + QB * 32 - 1, Tn - 1);
+    const int lo_w = active ? __builtin_amdgcn_readfirstlane(a.tok_start[min(wq0, Tn - 1)]) : 0;
+    const int st_hi = active ? __builtin_amdgcn_readfirstlane(a.tok_start[hi_w]) : 0;
+    const int lo = __builtin_amdgcn_readfirstlane(a.tok_start[q_tile0]);
+    const int hi = min(q_tile0 + QT - 1, Tn - 1);
+    const int u_lo = lo / KT, u_hi = hi / KT;
+
+    // Q as the stationary B operand: lane (n,hh) holds Q[row n][16t + 8hh .. +8]
+    frag qf[QB][DC];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int t = 0; t < DC; ++t)
+            qf[qb][t] = gload_frag<T>(Qj + (int64_t)qc[qb] * geo.q_st + t * 16 + hh * 8);
+
+    f32x16 oacc[QB][DB];
+    float m[QB], l[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        m[qb] = -INFINITY;
+        l[qb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[qb][db][i] = 0.f;
+    }
+    const float c = geo.scale_log2;
+
+    tile_load_async<T, D, KT, NT>(sK(0), K0, geo.kv_st, u_lo * KT, Tn - 1, tid);
+    tile_load_async<T, D, KT, NT>(sV(0), V0, geo.kv_st, u_lo * KT, Tn - 1, tid);
+    int stage = 0;
+    for (int u = u_lo; u <= u_hi; ++u) {
+        wait_async_copies();
+        __syncthreads();   // tile u is in LDS for everyone; everyone is done with the other stage
+        if (u < u_hi) {
+            tile_load_async<T, D, KT, NT>(sK(stage ^ 1), K0, geo.kv_st, (u + 1) * KT, Tn - 1, tid);
+            tile_load_async<T, D, KT, NT>(sV(stage ^ 1), V0, geo.kv_st, (u + 1) * KT, Tn - 1, tid);
+        }
+        const int kv0 = u * KT;
+        if (active && kv0 <= hi_w && kv0 + KT - 1 >= lo_w) {
+            const char* tk = sK(stage);
+            const char* tv = sV(stage);
+            // S^T[kv, q] = K Q^T
+            f32x16 sacc[KB][QB];
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sacc[kb][qb][i] = 0.f;
+#pragma unroll
+            for (int t = 0; t < DC; ++t) {
+                frag kf[KB];
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) kf[kb] = frag_rowwise<T, D>(tk, kb * 32 + n, t * 16 + hh * 8);
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = mma(kf[kb], qf[qb][t], sacc[kb][qb]);
+            }
+            // mask (only tiles that touch the diagonal or a document start of this wave's rows)
+            if (kv0 + KT - 1 > wq0 || kv0 < st_hi) {
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const int kv = kv0 + kb * 32 + acc_row(i, hh);
+                            const bool ok = kv <= qi[qb] && kv >= st[qb];
+                            sacc[kb][qb][i] = ok ? sacc[kb][qb][i] : -INFINITY;
+                        }
+            }
+            // online softmax, one query row per lane.  The reference maximum m[] is only moved
+            // (and O, l rescaled) when a row's tile maximum exceeds it by more than 2^kLazy, so the
+            // accumulator rescale is a rare, wave-uniform branch; p stays below 2^kLazy otherwise.
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                float mx = sacc[0][qb][0];
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][qb][i]);
+                mx = fmaxf(mx, xor32(mx));
+                const bool grow = (mx - m[qb]) * c > kLazy;   // false while everything is masked (-inf)
+                if (__any(grow)) {
+                    const float m_new = grow ? mx : m[qb];
+                    const float alpha = grow ? fast_exp2((m[qb] - m_new) * c) : 1.f;   // m = -inf -> 0
+                    m[qb] = m_new;
+                    l[qb] *= alpha;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
+                }
+                const float mc = m[qb] == -INFINITY ? 0.f : m[qb] * c;
+                float sum = 0.f;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float p = fast_exp2(fmaf(sacc[kb][qb][i], c, -mc));
+                        sacc[kb][qb][i] = p;
+                        sum += p;
+                    }
+                l[qb] += sum;
+            }
+            // O^T[d, q] += V^T P^T
+#pragma unroll
+            for (int c4 = 0; c4 < KT / 16; ++c4) {
+                frag pf[QB];
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) pf[qb] = acc_chunk<T>(sacc[c4 / 2][qb], c4 % 2);
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const frag vf = frag_transposed<T, D>(tv, c4 * 16, db * 32, lane);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) oacc[qb][db] = mma(vf, pf[qb], oacc[qb][db]);
+                }
+            }
+        }
+        stage ^= 1;
+    }
+
+    if (!active) return;
+
+    // diagonal keys of blocks 1..j: one score per block, per row
+    for (int lb = 1; lb <= j; ++lb) {
+        const T* Kl = static_cast<const T*>(a.k[lb]) + (int64_t)g * geo.kv_sh;
+        const T* Vl = static_cast<const T*>(a.v[lb]) + (int64_t)g * geo.kv_sh;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const T* krow = Kl + (int64_t)qc[qb] * geo.kv_st;
+            const T* vrow = Vl + (int64_t)qc[qb] * geo.kv_st;
+            float s = 0.f;
+#pragma unroll
+            for (int t = 0; t < DC; ++t) {
+                const frag kf = gload_frag<T>(krow + t * 16 + hh * 8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s = fmaf(to_f32<T>(qf[qb][t][e]), to_f32<T>(kf[e]), s);
+            }
+            s += xor32(s);
+            const float m_new = fmaxf(m[qb], s);
+            const float alpha = fast_exp2((m[qb] - m_new) * c);
+            const float p = fast_exp2((s - m_new) * c);
+            l[qb] = l[qb] * alpha + 0.5f * p;   // the two lane halves are added at the end
+            m[qb] = m_new;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const typename E::vec4 vv = gload_vec4<T>(vrow + db * 32 + i4 * 8 + hh * 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        oacc[qb][db][i4 * 4 + e] = fmaf(p, to_f32<T>(vv[e]), oacc[qb][db][i4 * 4 + e] * alpha);
+                }
+        }
+    }
+
+    // normalise and store
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float lt = l[qb] + xor32(l[qb]);
+        const float inv = 1.f / lt;
+        if (qi[qb] < Tn) {
+            T* orow = static_cast<T*>(a.o[j]) + (int64_t)h * geo.q_sh + (int64_t)qi[qb] * geo.q_st;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4)
+                    gstore_vec4<T>(orow + db * 32 + i4 * 8 + hh * 4, oacc[qb][db][i4 * 4 + 0] * inv,
+                                   oacc[qb][db][i4 * 4 + 1] * inv, oacc[qb][db][i4 * 4 + 2] * inv,
+                                   oacc[qb][db][i4 * 4 + 3] * inv);
+            if (hh == 0) a.lse[j][(int64_t)h * Tn + qi[qb]] = m[qb] * geo.scale + __logf(lt);
+        }
+    }
+}
+
+// first / one-past-last token of each token's document, by binary search in cu_seqlens
+__global__ void ttt_tok_bounds_kernel(const int* __restrict__ cu, int n_docs, int T, int* __restrict__ tok_start,
+                                      int* __restrict__ tok_end) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= T) return;
+    int lo = 0, hi = n_docs;   // find the largest r with cu[r] <= i (then cu[r+1] > i)
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cu[mid] <= i) lo = mid; else hi = mid;
+    }
+    tok_start[i] = cu[lo];
+    tok_end[i] = cu[lo + 1];
+}
+
+hipError_t launch_tok_bounds(const int* cu_dev, int n_docs, int T, int* tok_start, int* tok_end, hipStream_t stream) {
+    if (T <= 0) return hipSuccess;
+    hipLaunchKernelGGL(ttt_tok_bounds_kernel, dim3((T + 255) / 256), dim3(256), 0, stream, cu_dev, n_docs, T, tok_start,
+                       tok_end);
+    return hipGetLastError();
+}
+
+template <typename T, int D, int QB, int NW> struct FwdCfg {
+    static constexpr int kQT = NW * QB * 32;
+    static constexpr int kLds = 4 * 64 * D * (int)sizeof(T);
+};
+
+template <typename T, int D, int QB, int NW> static hipError_t launch_fwd_t(FwdArgs& a, hipStream_t stream) {
+    using C = FwdCfg<T, D, QB, NW>;
+    auto kern = ttt_fwd_kernel<T, D, QB, NW>;
+    static bool attr_done = false;   // benign race: the attribute is idempotent
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const Geometry& geo = a.geo;
+    a.n_tiles = (geo.T + C::kQT - 1) / C::kQT;
+    a.map.hkv = geo.hkv;
+    a.map.rest_count = a.n_tiles * geo.n_steps * geo.G;
+    int64_t grid;
+    if (geo.hkv % 8 == 0) {
+        a.map.mode = 1;
+        grid = (int64_t)geo.hkv * a.map.rest_count;
+    } else if (8 % geo.hkv == 0) {
+        a.map.mode = 2;
+        const int xp = 8 / geo.hkv;
+        grid = 8 * (int64_t)((a.map.rest_count + xp - 1) / xp);
+    } else {
+        a.map.mode = 0;
+        grid = (int64_t)geo.hkv * a.map.rest_count;
+    }
+    if (grid <= 0) return hipSuccess;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), C::kLds, stream, a);
+    return hipGetLastError();
+}
+
+int fwd_q_tile(int dtype, int head_dim) {
+    (void)head_dim;
+    return dtype == 1 ? 256 : 128;
+}
+
+hipError_t launch_fwd(int dtype, int head_dim, FwdArgs& a, hipStream_t stream) {
+    if (dtype == 1 && head_dim == 128) return launch_fwd_t<__bf16, 128, 2, 4>(a, stream);
+    if (dtype == 1 && head_dim == 64) return launch_fwd_t<__bf16, 64, 2, 4>(a, stream);
+    if (dtype == 0 && head_dim == 128) return launch_fwd_t<float, 128, 1, 4>(a, stream);
+    if (dtype == 0 && head_dim == 64) return launch_fwd_t<float, 64, 1, 4>(a, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace ttt
