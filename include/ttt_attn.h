@@ -139,6 +139,18 @@ int ttt_attn_bwd(const ttt_attn_params* params,
 /* Message of the calling thread's most recent failing call ("" if none).  Never NULL. */
 const char* ttt_attn_last_error(void);
 
+/*
+ * Diagnostics for measurement (not part of the method).  While enabled, ttt_attn_fwd/bwd bracket
+ * every kernel they launch with a pair of HIP events on the caller's stream (host-side objects
+ * only; still no device allocation and no synchronisation inside fwd/bwd).
+ * ttt_attn_profile_enable returns the previous setting.
+ * ttt_attn_profile_totals WAITS for the recorded events, adds the elapsed milliseconds up per
+ * kernel name into names[i] (static strings) / total_ms[i] / launches[i] for at most `capacity`
+ * distinct kernels, forgets the records and returns the number of names written.
+ */
+int ttt_attn_profile_enable(int on);
+int ttt_attn_profile_totals(int capacity, const char** names, float* total_ms, int32_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

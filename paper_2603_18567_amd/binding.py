@@ -17,7 +17,8 @@ TTT_F32, TTT_BF16 = 0, 1
 TTT_PASS_FWD, TTT_PASS_BWD, TTT_PASS_BWD_ACCUM = 0, 1, 2
 TTT_MAX_STEPS = 32
 
-EXPORTS = ("ttt_attn_workspace_bytes", "ttt_attn_fwd", "ttt_attn_bwd", "ttt_attn_last_error")
+EXPORTS = ("ttt_attn_workspace_bytes", "ttt_attn_fwd", "ttt_attn_bwd", "ttt_attn_last_error",
+           "ttt_attn_profile_enable", "ttt_attn_profile_totals")
 
 
 class TttAttnParams(ctypes.Structure):
@@ -61,12 +62,30 @@ def load_library():
                                      pp, pp, pp, ctypes.c_int, vp, ctypes.c_size_t, vp]
         lib.ttt_attn_last_error.restype = ctypes.c_char_p
         lib.ttt_attn_last_error.argtypes = []
+        lib.ttt_attn_profile_enable.restype = ctypes.c_int
+        lib.ttt_attn_profile_enable.argtypes = [ctypes.c_int]
+        lib.ttt_attn_profile_totals.restype = ctypes.c_int
+        lib.ttt_attn_profile_totals.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p),
+                                                ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32)]
         _lib = lib
     return _lib
 
 
 def ttt_attn_last_error() -> str:
     return load_library().ttt_attn_last_error().decode()
+
+
+def ttt_attn_profile_enable(on: bool) -> bool:
+    return bool(load_library().ttt_attn_profile_enable(int(bool(on))))
+
+
+def ttt_attn_profile_totals(capacity: int = 16) -> dict:
+    """{kernel name: total milliseconds} of the launches recorded since the last query (waits)."""
+    names = (ctypes.c_char_p * capacity)()
+    ms = (ctypes.c_float * capacity)()
+    cnt = (ctypes.c_int32 * capacity)()
+    n = load_library().ttt_attn_profile_totals(capacity, names, ms, cnt)
+    return {names[i].decode(): float(ms[i]) for i in range(n)}
 
 
 def _ptr_array(tensors, k):

@@ -6,6 +6,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
 
 #include "../../include/ttt_attn.h"
 #include "ttt_args.hpp"
@@ -110,9 +113,80 @@ int check_workspace(const void* ws, size_t have, size_t need) {
     return TTT_OK;
 }
 
+// ---- diagnostics: per-kernel HIP-event timing, off unless a caller turns it on
+struct ProfileRecord {
+    const char* name;
+    hipEvent_t start, stop;
+};
+std::mutex g_prof_mutex;
+bool g_prof_on = false;
+std::vector<ProfileRecord> g_prof_records;
+thread_local ProfileRecord g_prof_open = {nullptr, nullptr, nullptr};
+
 }  // namespace
 
+namespace ttt {
+
+void profile_begin(const char* kernel_name, hipStream_t stream) {
+    g_prof_open.name = nullptr;
+    if (!g_prof_on) return;
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) return;
+    if (hipEventCreate(&b) != hipSuccess) {
+        (void)hipEventDestroy(a);
+        return;
+    }
+    (void)hipEventRecord(a, stream);
+    g_prof_open = {kernel_name, a, b};
+}
+
+void profile_end(hipStream_t stream) {
+    if (!g_prof_open.name) return;
+    (void)hipEventRecord(g_prof_open.stop, stream);
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    g_prof_records.push_back(g_prof_open);
+    g_prof_open.name = nullptr;
+}
+
+}  // namespace ttt
+
 extern "C" {
+
+int ttt_attn_profile_enable(int on) {
+    std::lock_guard<std::mutex> lock(g_prof_mutex);
+    const int was = g_prof_on ? 1 : 0;
+    g_prof_on = on != 0;
+    return was;
+}
+
+int ttt_attn_profile_totals(int capacity, const char** names, float* total_ms, int32_t* launches) {
+    std::vector<ProfileRecord> recs;
+    {
+        std::lock_guard<std::mutex> lock(g_prof_mutex);
+        recs.swap(g_prof_records);
+    }
+    int n = 0;
+    for (const ProfileRecord& r : recs) {
+        float ms = 0.f;
+        const bool ok = hipEventSynchronize(r.stop) == hipSuccess && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess;
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+        if (!ok) continue;
+        int slot = -1;
+        for (int i = 0; i < n; ++i)
+            if (std::strcmp(names[i], r.name) == 0) slot = i;
+        if (slot < 0) {
+            if (n >= capacity) continue;
+            slot = n++;
+            names[slot] = r.name;
+            total_ms[slot] = 0.f;
+            launches[slot] = 0;
+        }
+        total_ms[slot] += ms;
+        launches[slot] += 1;
+    }
+    return n;
+}
 
 const char* ttt_attn_last_error(void) { return g_err; }
 

@@ -63,7 +63,14 @@ hipError_t launch_tok_bounds(const int* cu_dev, int n_docs, int T, int* tok_star
 hipError_t launch_fwd(int dtype, int head_dim, FwdArgs& a, hipStream_t stream);
 hipError_t launch_bwd(int dtype, int head_dim, BwdArgs& a, hipStream_t stream);
 
-// tile heights the host needs for grid sizes
-int fwd_q_tile(int dtype, int head_dim);
+// Diagnostics (off by default): brackets one kernel launch with HIP events on its stream so that
+// a caller can read per-kernel durations afterwards (ttt_attn_profile_totals).
+void profile_begin(const char* kernel_name, hipStream_t stream);
+void profile_end(hipStream_t stream);
+struct ProfileScope {
+    hipStream_t stream;
+    ProfileScope(const char* name, hipStream_t s) : stream(s) { profile_begin(name, s); }
+    ~ProfileScope() { profile_end(stream); }
+};
 
 }  // namespace ttt

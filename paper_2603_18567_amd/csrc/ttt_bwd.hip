@@ -538,6 +538,7 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
     // 1. clear the block-0 accumulators unless a carry from later steps is being continued
     if (!a.accumulate || a.carry_reset) {
         const int blocks = (int)((acc_n4 + 255) / 256 < 4096 ? (acc_n4 + 255) / 256 : 4096);
+        ProfileScope prof("ttt_fill_zero_kernel", stream);
         hipLaunchKernelGGL(ttt_fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<f32x4*>(a.dk0_acc), acc_n4);
         hipLaunchKernelGGL(ttt_fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<f32x4*>(a.dv0_acc), acc_n4);
         if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -555,7 +556,10 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
             e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, stream, a);
+        {
+            ProfileScope prof("ttt_bwd_pre_kernel", stream);
+            hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, stream, a);
+        }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
 
@@ -574,7 +578,10 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         int64_t grid;
         set_head_map(a.map, geo.hkv, a.n_tiles * geo.n_steps * geo.G, grid);
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW_DQ * 64), LDS, stream, a);
+        {
+            ProfileScope prof("ttt_bwd_dq_kernel", stream);
+            hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW_DQ * 64), LDS, stream, a);
+        }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
 
@@ -598,14 +605,20 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         int64_t grid;
         set_head_map(a.map, geo.hkv, a.n_tiles * n_split, grid);
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW_KV * 64), LDS, stream, a);
+        {
+            ProfileScope prof("ttt_bwd_dkv_kernel", stream);
+            hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW_KV * 64), LDS, stream, a);
+        }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
 
     // 5. block-0 sums -> output dtype, once the sweep has covered step 0
     if (!a.accumulate || geo.step_begin == 0) {
         const int blocks = (int)((acc_n4 + 255) / 256 < 4096 ? (acc_n4 + 255) / 256 : 4096);
-        hipLaunchKernelGGL((ttt_bwd_finish_kernel<T, D>), dim3(blocks), dim3(256), 0, stream, a);
+        {
+            ProfileScope prof("ttt_bwd_finish_kernel", stream);
+            hipLaunchKernelGGL((ttt_bwd_finish_kernel<T, D>), dim3(blocks), dim3(256), 0, stream, a);
+        }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;

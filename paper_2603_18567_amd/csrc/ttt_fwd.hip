@@ -256,6 +256,7 @@ __global__ void ttt_tok_bounds_kernel(const int* __restrict__ cu, int n_docs, in
 
 hipError_t launch_tok_bounds(const int* cu_dev, int n_docs, int T, int* tok_start, int* tok_end, hipStream_t stream) {
     if (T <= 0) return hipSuccess;
+    ProfileScope prof("ttt_tok_bounds_kernel", stream);
     hipLaunchKernelGGL(ttt_tok_bounds_kernel, dim3((T + 255) / 256), dim3(256), 0, stream, cu_dev, n_docs, T, tok_start,
                        tok_end);
     return hipGetLastError();
@@ -293,13 +294,9 @@ template <typename T, int D, int QB, int NW> static hipError_t launch_fwd_t(FwdA
     }
     if (grid <= 0) return hipSuccess;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    ProfileScope prof("ttt_fwd_kernel", stream);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), C::kLds, stream, a);
     return hipGetLastError();
-}
-
-int fwd_q_tile(int dtype, int head_dim) {
-    (void)head_dim;
-    return dtype == 1 ? 256 : 128;
 }
 
 hipError_t launch_fwd(int dtype, int head_dim, FwdArgs& a, hipStream_t stream) {

@@ -11,8 +11,10 @@ from paper_2603_18567_amd.workloads import make_inputs
 
 # Tolerances (benchmark spec): fp32 inputs max-abs 1e-4 on every output; bf16 inputs
 # max-abs error <= 2e-2 * max|reference| per tensor, LSE absolute 1e-3 (both sides see the same
-# rounded inputs; LSE is fp32 on the GPU).
-TOL = {"f32": dict(kind="abs", val=1e-4, lse=1e-4), "bf16": dict(kind="rel", val=2e-2, lse=1e-3)}
+# rounded inputs; LSE is fp32 on the GPU).  A tensor whose reference is identically zero (e.g. dQ_0
+# of length-1 documents, where p = 1 and ds = p (dp - D) = 0) has no scale of its own: there the
+# bound is the absolute floor 1e-5, about 10 fp32 ulps of the O(1) terms that cancel in dp - D.
+TOL = {"f32": dict(kind="abs", val=1e-4, lse=1e-4), "bf16": dict(kind="rel", val=2e-2, lse=1e-3, floor=1e-5)}
 
 
 def to_np32(t):
@@ -50,7 +52,7 @@ def check(name, got, ref, dtype, lse=False):
     elif tol["kind"] == "abs":
         bound = tol["val"]
     else:
-        bound = tol["val"] * float(np.abs(ref).max())
+        bound = max(tol["val"] * float(np.abs(ref).max()), tol["floor"])
     assert err <= bound, f"{name}: max abs err {err:.3e} > bound {bound:.3e}"
     return err, bound
 
