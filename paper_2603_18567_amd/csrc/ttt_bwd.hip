@@ -625,7 +625,7 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
 }
 
 hipError_t launch_bwd(int dtype, int head_dim, BwdArgs& a, hipStream_t stream) {
-    if (dtype == 1 && head_dim == 128) return launch_bwd_t<__bf16, 128, 1, 4, 4>(a, stream);
+    if (dtype == 1 && head_dim == 128) return launch_bwd_t<__bf16, 128, 1, 8, 4>(a, stream);
     if (dtype == 1 && head_dim == 64) return launch_bwd_t<__bf16, 64, 1, 4, 4>(a, stream);
     if (dtype == 0 && head_dim == 128) return launch_bwd_t<float, 128, 1, 4, 4>(a, stream);
     if (dtype == 0 && head_dim == 64) return launch_bwd_t<float, 64, 1, 4, 4>(a, stream);

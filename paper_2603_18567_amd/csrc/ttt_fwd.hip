@@ -300,7 +300,7 @@ template <typename T, int D, int QB, int NW> static hipError_t launch_fwd_t(FwdA
 }
 
 hipError_t launch_fwd(int dtype, int head_dim, FwdArgs& a, hipStream_t stream) {
-    if (dtype == 1 && head_dim == 128) return launch_fwd_t<__bf16, 128, 2, 4>(a, stream);
+    if (dtype == 1 && head_dim == 128) return launch_fwd_t<__bf16, 128, 1, 8>(a, stream);
     if (dtype == 1 && head_dim == 64) return launch_fwd_t<__bf16, 64, 2, 4>(a, stream);
     if (dtype == 0 && head_dim == 128) return launch_fwd_t<float, 128, 1, 4>(a, stream);
     if (dtype == 0 && head_dim == 64) return launch_fwd_t<float, 64, 1, 4>(a, stream);
