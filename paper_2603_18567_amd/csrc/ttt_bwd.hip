@@ -419,16 +419,38 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_kernel(const BwdArgs a) {
             for (int qb = 0; qb < QTL / 32; ++qb) {
                 const int qb0 = q0 + qb * 32;
                 if (qb0 + 31 < wk0 || qb0 >= wq_end) continue;
+                // bf16: all LDS reads of the block are issued up front (row-wise fragments for S and
+                // dP, transposed ones for dV and dK) so that their latency hides behind the matrix
+                // work; fp32 fragments are twice as large and are read where they are used
+                constexpr bool kUpfront = sizeof(T) == 2;
+                frag qa[DC], ga[DC], gt[2][DB], qt[2][DB];
+                if constexpr (kUpfront) {
+#pragma unroll
+                    for (int t = 0; t < DC; ++t) {
+                        qa[t] = frag_rowwise<T, D>(tq, qb * 32 + n, t * 16 + hh * 8);
+                        ga[t] = frag_rowwise<T, D>(tg, qb * 32 + n, t * 16 + hh * 8);
+                    }
+#pragma unroll
+                    for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+                        for (int db = 0; db < DB; ++db) {
+                            gt[c2][db] = frag_transposed<T, D>(tg, qb * 32 + c2 * 16, db * 32, lane);
+                            qt[c2][db] = frag_transposed<T, D>(tq, qb * 32 + c2 * 16, db * 32, lane);
+                        }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 // S[q, kv] = Q K^T and dP[q, kv] = dO V^T : lane = kv column, values = query rows
                 f32x16 sacc, pacc;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sacc[i] = pacc[i] = 0.f;
 #pragma unroll
                 for (int t = 0; t < DC; ++t) {
-                    const frag qa = frag_rowwise<T, D>(tq, qb * 32 + n, t * 16 + hh * 8);
-                    const frag ga = frag_rowwise<T, D>(tg, qb * 32 + n, t * 16 + hh * 8);
-                    sacc = mma(qa, kf[t], sacc);
-                    pacc = mma(ga, vf[t], pacc);
+                    if constexpr (!kUpfront) {
+                        qa[t] = frag_rowwise<T, D>(tq, qb * 32 + n, t * 16 + hh * 8);
+                        ga[t] = frag_rowwise<T, D>(tg, qb * 32 + n, t * 16 + hh * 8);
+                    }
+                    sacc = mma(qa[t], kf[t], sacc);
+                    pacc = mma(ga[t], vf[t], pacc);
                 }
                 // every row of the block sees every key of the wave iff the block is below the
                 // wave's last key and starts its document at or before the wave's first key
@@ -457,10 +479,12 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_kernel(const BwdArgs a) {
                     const frag sf = acc_chunk<T>(pacc, c2);
 #pragma unroll
                     for (int db = 0; db < DB; ++db) {
-                        const frag gt = frag_transposed<T, D>(tg, qb * 32 + c2 * 16, db * 32, lane);
-                        const frag qt = frag_transposed<T, D>(tq, qb * 32 + c2 * 16, db * 32, lane);
-                        dvacc[db] = mma(pf, gt, dvacc[db]);
-                        dkacc[db] = mma(sf, qt, dkacc[db]);
+                        if constexpr (!kUpfront) {
+                            gt[c2][db] = frag_transposed<T, D>(tg, qb * 32 + c2 * 16, db * 32, lane);
+                            qt[c2][db] = frag_transposed<T, D>(tq, qb * 32 + c2 * 16, db * 32, lane);
+                        }
+                        dvacc[db] = mma(pf, gt[c2][db], dvacc[db]);
+                        dkacc[db] = mma(sf, qt[c2][db], dkacc[db]);
                     }
                 }
             }

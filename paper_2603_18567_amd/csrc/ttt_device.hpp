@@ -153,6 +153,60 @@ template <> TTT_DEV f32x8 frag_transposed<float, 64>(const char* tile, int row0,
     return frag_transposed_f32<64>(tile, row0, col0, lane);
 }
 
+// ---- per-lane fragment addressing, computed once per kernel.  The swizzle involves row bits 0..3
+// only, so stepping by whole 16-row chunks (transposed reads) or 32-row blocks (row-wise reads) and
+// switching tiles or pipeline stages adds compile-time constants, which the LDS instructions carry
+// in their immediate offset field: no address arithmetic is left in the inner loops.
+template <typename T, int D> struct LaneFrags {
+    using frag = typename Elem<T>::frag;
+    int lane;
+    TTT_DEV void init(int lane_) { lane = lane_; }
+    TTT_DEV frag rowwise(const char* tile, int rb, int t) const {
+        return frag_rowwise<T, D>(tile, rb * 32 + (lane & 31), t * 16 + (lane >> 5) * 8);
+    }
+    TTT_DEV frag transposed(const char* tile, int c16, int db) const {
+        return frag_transposed<T, D>(tile, c16 * 16, db * 32, lane);
+    }
+};
+template <int D> struct LaneFrags<__bf16, D> {
+    using TL = Tile<__bf16, D>;
+    uint32_t row[D / 16];      // fragment t of row lane%32
+    uint32_t tr[D / 32][2];    // 4-element piece this lane addresses in 32-column block db, rows +0 / +8
+    TTT_DEV void init(int lane) {
+        const int n = lane & 31, hh = lane >> 5;
+#pragma unroll
+        for (int t = 0; t < D / 16; ++t) row[t] = TL::offset(n, t * 16 + hh * 8);
+        const int q = lane & 15, grp = (lane >> 4) & 1;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) {
+            tr[db][0] = TL::offset(4 * hh + (q >> 2), db * 32 + 16 * grp + 4 * (q & 3));
+            tr[db][1] = TL::offset(4 * hh + (q >> 2) + 8, db * 32 + 16 * grp + 4 * (q & 3));
+        }
+    }
+    TTT_DEV bf16x8 rowwise(const char* tile, int rb, int t) const {
+        return *reinterpret_cast<const bf16x8*>(tile + rb * 32 * TL::kRowBytes + row[t]);
+    }
+    TTT_DEV bf16x8 transposed(const char* tile, int c16, int db) const {
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        const char* base = tile + c16 * 16 * TL::kRowBytes;
+        union { s16x4 s[2]; bf16x8 v; } u;
+        u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(base + tr[db][0]));
+        u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(base + tr[db][1]));
+        return u.v;
+    }
+};
+
+// Ordering fence for the compiler only (no instruction): memory operations -- in particular LDS
+// reads requested ahead of their use -- stay on their side of it, and the instruction scheduler does
+// not move anything across it.
+TTT_DEV void issue_fence() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// compile-time integer handed to generic lambdas (pipeline stage)
+template <int V> struct IntC { static constexpr int value = V; };
+
 // ---- global -> LDS tile copy without passing through registers (16 bytes per lane per
 // instruction; one wave instruction fills 1024 contiguous LDS bytes).  ROWS*kRowBytes must be a
 // multiple of NTHREADS*16.  Rows are clamped to [0, max_row] so the copy never leaves the tensor;
@@ -185,6 +239,17 @@ TTT_DEV void wait_async_copies() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vm
 
 // ---- small helpers
 TTT_DEV float xor32(float v) { return __shfl_xor(v, 32, 64); }
+// max / sum of a value with its partner in the other lane half (lane ^ 32), on the vector ALU:
+// v_permlane32_swap exchanges the upper half of one register with the lower half of the other, so
+// swapping a value with itself yields {lower-half copy, upper-half copy} in every lane.
+TTT_DEV float half_max(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+TTT_DEV float half_sum(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 TTT_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 template <typename T> TTT_DEV float to_f32(T v);

@@ -16,8 +16,8 @@
 
 namespace ttt {
 
-template <typename T, int D, int QB, int NW>
-__global__ __launch_bounds__(NW * 64) void ttt_fwd_kernel(const FwdArgs a) {
+template <typename T, int D, int QB, int NW, int MINB>
+__global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a) {
     using E = Elem<T>;
     using frag = typename E::frag;
     constexpr int KT = 64;                // kv rows per LDS tile
@@ -90,152 +90,195 @@ __global__ __launch_bounds__(NW * 64) void ttt_fwd_kernel(const FwdArgs a) {
     }
     const float c = geo.scale_log2;
 
-    tile_load_async<T, D, KT, NT>(sK(0), K0, geo.kv_st, u_lo * KT, Tn - 1, tid);
-    tile_load_async<T, D, KT, NT>(sV(0), V0, geo.kv_st, u_lo * KT, Tn - 1, tid);
-    int stage = 0;
-    for (int u = u_lo; u <= u_hi; ++u) {
+    LaneFrags<T, D> lf;
+    lf.init(lane);
+
+    // one kv tile: wait for its copy, start the next one into the other stage, compute from this one
+    auto step = [&](auto stage_c, int u) {
+        constexpr int ST = decltype(stage_c)::value;
         wait_async_copies();
         __syncthreads();   // tile u is in LDS for everyone; everyone is done with the other stage
         if (u < u_hi) {
-            tile_load_async<T, D, KT, NT>(sK(stage ^ 1), K0, geo.kv_st, (u + 1) * KT, Tn - 1, tid);
-            tile_load_async<T, D, KT, NT>(sV(stage ^ 1), V0, geo.kv_st, (u + 1) * KT, Tn - 1, tid);
+            tile_load_async<T, D, KT, NT>(sK(ST ^ 1), K0, geo.kv_st, (u + 1) * KT, Tn - 1, tid);
+            tile_load_async<T, D, KT, NT>(sV(ST ^ 1), V0, geo.kv_st, (u + 1) * KT, Tn - 1, tid);
         }
         const int kv0 = u * KT;
-        if (active && kv0 <= hi_w && kv0 + KT - 1 >= lo_w) {
-            const char* tk = sK(stage);
-            const char* tv = sV(stage);
-            // S^T[kv, q] = K Q^T
-            f32x16 sacc[KB][QB];
+        if (!(active && kv0 <= hi_w && kv0 + KT - 1 >= lo_w)) return;
+        const char* tk = smem + ST * TILE_BYTES;
+        const char* tv = smem + (2 + ST) * TILE_BYTES;
+        // S^T[kv, q] = K Q^T
+        f32x16 sacc[KB][QB];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[kb][qb][i] = 0.f;
+#pragma unroll
+        for (int t = 0; t < DC; ++t) {
+            frag kf[KB];
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) kf[kb] = lf.rowwise(tk, kb, t);
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = mma(kf[kb], qf[qb][t], sacc[kb][qb]);
+        }
+        // mask (only tiles that touch the diagonal or a document start of this wave's rows)
+        if (kv0 + KT - 1 > wq0 || kv0 < st_hi) {
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) sacc[kb][qb][i] = 0.f;
-#pragma unroll
-            for (int t = 0; t < DC; ++t) {
-                frag kf[KB];
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb) kf[kb] = frag_rowwise<T, D>(tk, kb * 32 + n, t * 16 + hh * 8);
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) sacc[kb][qb] = mma(kf[kb], qf[qb][t], sacc[kb][qb]);
-            }
-            // mask (only tiles that touch the diagonal or a document start of this wave's rows)
-            if (kv0 + KT - 1 > wq0 || kv0 < st_hi) {
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const int kv = kv0 + kb * 32 + acc_row(i, hh);
-                            const bool ok = kv <= qi[qb] && kv >= st[qb];
-                            sacc[kb][qb][i] = ok ? sacc[kb][qb][i] : -INFINITY;
-                        }
-            }
-            // online softmax, one query row per lane.  The reference maximum m[] is only moved
-            // (and O, l rescaled) when a row's tile maximum exceeds it by more than 2^kLazy, so the
-            // accumulator rescale is a rare, wave-uniform branch; p stays below 2^kLazy otherwise.
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                float mx = sacc[0][qb][0];
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][qb][i]);
-                mx = fmaxf(mx, xor32(mx));
-                const bool grow = (mx - m[qb]) * c > kLazy;   // false while everything is masked (-inf)
-                if (__any(grow)) {
-                    const float m_new = grow ? mx : m[qb];
-                    const float alpha = grow ? fast_exp2((m[qb] - m_new) * c) : 1.f;   // m = -inf -> 0
-                    m[qb] = m_new;
-                    l[qb] *= alpha;
-#pragma unroll
-                    for (int db = 0; db < DB; ++db)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
-                }
-                const float mc = m[qb] == -INFINITY ? 0.f : m[qb] * c;
-                float sum = 0.f;
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const float p = fast_exp2(fmaf(sacc[kb][qb][i], c, -mc));
-                        sacc[kb][qb][i] = p;
-                        sum += p;
+                        const int kv = kv0 + kb * 32 + acc_row(i, hh);
+                        const bool ok = kv <= qi[qb] && kv >= st[qb];
+                        sacc[kb][qb][i] = ok ? sacc[kb][qb][i] : -INFINITY;
                     }
-                l[qb] += sum;
-            }
-            // O^T[d, q] += V^T P^T
-#pragma unroll
-            for (int c4 = 0; c4 < KT / 16; ++c4) {
-                frag pf[QB];
-#pragma unroll
-                for (int qb = 0; qb < QB; ++qb) pf[qb] = acc_chunk<T>(sacc[c4 / 2][qb], c4 % 2);
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const frag vf = frag_transposed<T, D>(tv, c4 * 16, db * 32, lane);
-#pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) oacc[qb][db] = mma(vf, pf[qb], oacc[qb][db]);
-                }
-            }
         }
-        stage ^= 1;
-    }
-
-    if (!active) return;
-
-    // diagonal keys of blocks 1..j: one score per block, per row
-    for (int lb = 1; lb <= j; ++lb) {
-        const T* Kl = static_cast<const T*>(a.k[lb]) + (int64_t)g * geo.kv_sh;
-        const T* Vl = static_cast<const T*>(a.v[lb]) + (int64_t)g * geo.kv_sh;
+        // online softmax, one query row per lane.  The reference maximum m[] is only moved (and O, l
+        // rescaled) when a row's tile maximum exceeds it by more than 2^kLazy, so the accumulator
+        // rescale is a rare, wave-uniform branch; p stays below 2^kLazy otherwise.
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            const T* krow = Kl + (int64_t)qc[qb] * geo.kv_st;
-            const T* vrow = Vl + (int64_t)qc[qb] * geo.kv_st;
-            float s = 0.f;
+            float mx = sacc[0][qb][0];
 #pragma unroll
-            for (int t = 0; t < DC; ++t) {
-                const frag kf = gload_frag<T>(krow + t * 16 + hh * 8);
+            for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) s = fmaf(to_f32<T>(qf[qb][t][e]), to_f32<T>(kf[e]), s);
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][qb][i]);
+            mx = half_max(mx);
+            const bool grow = (mx - m[qb]) * c > kLazy;   // false while everything is masked (-inf)
+            if (__any(grow)) {
+                const float m_new = grow ? mx : m[qb];
+                const float alpha = grow ? fast_exp2((m[qb] - m_new) * c) : 1.f;   // m = -inf -> 0
+                m[qb] = m_new;
+                l[qb] *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
             }
-            s += xor32(s);
-            const float m_new = fmaxf(m[qb], s);
-            const float alpha = fast_exp2((m[qb] - m_new) * c);
-            const float p = fast_exp2((s - m_new) * c);
-            l[qb] = l[qb] * alpha + 0.5f * p;   // the two lane halves are added at the end
-            m[qb] = m_new;
+            const float mc = m[qb] == -INFINITY ? 0.f : m[qb] * c;
+            float sum = 0.f;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+            for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    const typename E::vec4 vv = gload_vec4<T>(vrow + db * 32 + i4 * 8 + hh * 4);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        oacc[qb][db][i4 * 4 + e] = fmaf(p, to_f32<T>(vv[e]), oacc[qb][db][i4 * 4 + e] * alpha);
+                for (int i = 0; i < 16; ++i) {
+                    const float p = fast_exp2(fmaf(sacc[kb][qb][i], c, -mc));
+                    sacc[kb][qb][i] = p;
+                    sum += p;
                 }
+            l[qb] += sum;
+        }
+        // O^T[d, q] += V^T P^T
+#pragma unroll
+        for (int c4 = 0; c4 < KT / 16; ++c4) {
+            frag pf[QB];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) pf[qb] = acc_chunk<T>(sacc[c4 / 2][qb], c4 % 2);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const frag vf = lf.transposed(tv, c4, db);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) oacc[qb][db] = mma(vf, pf[qb], oacc[qb][db]);
+            }
+        }
+    };
+
+    tile_load_async<T, D, KT, NT>(sK(0), K0, geo.kv_st, u_lo * KT, Tn - 1, tid);
+    tile_load_async<T, D, KT, NT>(sV(0), V0, geo.kv_st, u_lo * KT, Tn - 1, tid);
+
+    // Diagonal keys of blocks 1..j (suffix part of the mask): one key per block and row, taken first
+    // so that their global-memory latency overlaps the first tile copy.  Row-wise dot products on
+    // the vector ALU; the fragments of block lb+1 are requested before block lb is consumed.
+    if (active && j >= 1) {
+        frag dk[QB][DC];
+        typename E::vec4 dv[QB][DB][4];
+        auto request = [&](int lb) {
+            const T* Kl = static_cast<const T*>(a.k[lb]) + (int64_t)g * geo.kv_sh;
+            const T* Vl = static_cast<const T*>(a.v[lb]) + (int64_t)g * geo.kv_sh;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                const T* krow = Kl + (int64_t)qc[qb] * geo.kv_st;
+                const T* vrow = Vl + (int64_t)qc[qb] * geo.kv_st;
+#pragma unroll
+                for (int t = 0; t < DC; ++t) dk[qb][t] = gload_frag<T>(krow + t * 16 + hh * 8);
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) dv[qb][db][i4] = gload_vec4<T>(vrow + db * 32 + i4 * 8 + hh * 4);
+            }
+        };
+        request(1);
+        for (int lb = 1; lb <= j; ++lb) {
+            float s[QB];
+            float vv[QB][DB][16];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                s[qb] = 0.f;
+#pragma unroll
+                for (int t = 0; t < DC; ++t)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) s[qb] = fmaf(to_f32<T>(qf[qb][t][e]), to_f32<T>(dk[qb][t][e]), s[qb]);
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) vv[qb][db][i] = to_f32<T>(dv[qb][db][i / 4][i % 4]);
+            }
+            if (lb < j) request(lb + 1);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                const float sc = half_sum(s[qb]);
+                const float m_new = fmaxf(m[qb], sc);
+                const float alpha = fast_exp2((m[qb] - m_new) * c);   // first key: exp2(-inf) = 0
+                const float p = fast_exp2((sc - m_new) * c);
+                l[qb] = l[qb] * alpha + 0.5f * p;   // the two lane halves are added at the end
+                m[qb] = m_new;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[qb][db][i] = fmaf(p, vv[qb][db][i], oacc[qb][db][i] * alpha);
+            }
         }
     }
 
-    // normalise and store
+    for (int u = u_lo; u <= u_hi; u += 2) {
+        step(IntC<0>{}, u);
+        if (u + 1 <= u_hi) step(IntC<1>{}, u + 1);
+    }
+
+    // normalise; rows go through a wave-private LDS patch (carved out of the tile stages, which
+    // everybody has finished reading after this barrier) so that every global store is a full
+    // 16-byte piece of a row and a wave instruction covers whole rows
+    __syncthreads();
+    if (!active) return;
+    char* patch = smem + wave * (32 * D * E::kBytes);
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const float lt = l[qb] + xor32(l[qb]);
+        const float lt = half_sum(l[qb]);
         const float inv = 1.f / lt;
-        if (qi[qb] < Tn) {
-            T* orow = static_cast<T*>(a.o[j]) + (int64_t)h * geo.q_sh + (int64_t)qi[qb] * geo.q_st;
+        if (hh == 0 && qi[qb] < Tn) a.lse[j][(int64_t)h * Tn + qi[qb]] = m[qb] * geo.scale + __logf(lt);
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4)
-                    gstore_vec4<T>(orow + db * 32 + i4 * 8 + hh * 4, oacc[qb][db][i4 * 4 + 0] * inv,
-                                   oacc[qb][db][i4 * 4 + 1] * inv, oacc[qb][db][i4 * 4 + 2] * inv,
-                                   oacc[qb][db][i4 * 4 + 3] * inv);
-            if (hh == 0) a.lse[j][(int64_t)h * Tn + qi[qb]] = m[qb] * geo.scale + __logf(lt);
+            for (int i4 = 0; i4 < 4; ++i4) {
+                T* dst = reinterpret_cast<T*>(patch + Tile<T, D>::offset(n, db * 32 + i4 * 8 + hh * 4));
+                typename E::vec4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pk[e] = (T)(oacc[qb][db][i4 * 4 + e] * inv);
+                *reinterpret_cast<typename E::vec4*>(dst) = pk;
+            }
+        // the patch is private to the wave: LDS operations of one wave complete in order
+        constexpr int PIECES = Tile<T, D>::kPieces;
+        T* obase = static_cast<T*>(a.o[j]) + (int64_t)h * geo.q_sh;
+#pragma unroll
+        for (int it = 0; it < 32 * PIECES / 64; ++it) {
+            const int pidx = it * 64 + lane;
+            const int r = pidx / PIECES, piece = pidx % PIECES;
+            const int row = wq0 + 32 * qb + r;
+            const f32x4 val = *reinterpret_cast<const f32x4*>(patch + r * Tile<T, D>::kRowBytes + ((piece ^ Tile<T, D>::swz(r)) * 16));
+            if (row < Tn) *reinterpret_cast<f32x4*>(obase + (int64_t)row * geo.q_st + piece * Tile<T, D>::kElemsPerPiece) = val;
         }
     }
 }
@@ -262,14 +305,14 @@ hipError_t launch_tok_bounds(const int* cu_dev, int n_docs, int T, int* tok_star
     return hipGetLastError();
 }
 
-template <typename T, int D, int QB, int NW> struct FwdCfg {
+template <typename T, int D, int QB, int NW, int MINB> struct FwdCfg {
     static constexpr int kQT = NW * QB * 32;
-    static constexpr int kLds = 4 * 64 * D * (int)sizeof(T);
+    static constexpr int kLds = 4 * 64 * D * (int)sizeof(T);   // two stages of K and V tiles
 };
 
-template <typename T, int D, int QB, int NW> static hipError_t launch_fwd_t(FwdArgs& a, hipStream_t stream) {
-    using C = FwdCfg<T, D, QB, NW>;
-    auto kern = ttt_fwd_kernel<T, D, QB, NW>;
+template <typename T, int D, int QB, int NW, int MINB> static hipError_t launch_fwd_t(FwdArgs& a, hipStream_t stream) {
+    using C = FwdCfg<T, D, QB, NW, MINB>;
+    auto kern = ttt_fwd_kernel<T, D, QB, NW, MINB>;
     static bool attr_done = false;   // benign race: the attribute is idempotent
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
@@ -300,10 +343,10 @@ template <typename T, int D, int QB, int NW> static hipError_t launch_fwd_t(FwdA
 }
 
 hipError_t launch_fwd(int dtype, int head_dim, FwdArgs& a, hipStream_t stream) {
-    if (dtype == 1 && head_dim == 128) return launch_fwd_t<__bf16, 128, 1, 8>(a, stream);
-    if (dtype == 1 && head_dim == 64) return launch_fwd_t<__bf16, 64, 2, 4>(a, stream);
-    if (dtype == 0 && head_dim == 128) return launch_fwd_t<float, 128, 1, 4>(a, stream);
-    if (dtype == 0 && head_dim == 64) return launch_fwd_t<float, 64, 1, 4>(a, stream);
+    if (dtype == 1 && head_dim == 128) return launch_fwd_t<__bf16, 128, 1, 8, 1>(a, stream);
+    if (dtype == 1 && head_dim == 64) return launch_fwd_t<__bf16, 64, 2, 4, 1>(a, stream);
+    if (dtype == 0 && head_dim == 128) return launch_fwd_t<float, 128, 1, 4, 1>(a, stream);
+    if (dtype == 0 && head_dim == 64) return launch_fwd_t<float, 64, 1, 4, 1>(a, stream);
     return hipErrorInvalidValue;
 }
 
