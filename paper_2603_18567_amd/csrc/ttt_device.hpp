@@ -256,6 +256,21 @@ template <typename T> TTT_DEV float to_f32(T v);
 template <> TTT_DEV float to_f32<float>(float v) { return v; }
 template <> TTT_DEV float to_f32<__bf16>(__bf16 v) { return (float)v; }
 
+// acc + <a, b> over the 8 elements of two fragments (fp32 accumulation; bf16 pairs go through the
+// packed dot instruction, which needs no unpacking)
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+TTT_DEV float dot8(const bf16x8& a, const bf16x8& b, float acc) {
+#pragma unroll
+    for (int e = 0; e < 8; e += 2)
+        acc = __builtin_amdgcn_fdot2_f32_bf16(bf16x2{a[e], a[e + 1]}, bf16x2{b[e], b[e + 1]}, acc, false);
+    return acc;
+}
+TTT_DEV float dot8(const f32x8& a, const f32x8& b, float acc) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc = fmaf(a[e], b[e], acc);
+    return acc;
+}
+
 // load 8 consecutive elements from global as a fragment
 template <typename T> TTT_DEV typename Elem<T>::frag gload_frag(const T* p);
 template <> TTT_DEV bf16x8 gload_frag<__bf16>(const __bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }

@@ -213,32 +213,39 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
         request(1);
         for (int lb = 1; lb <= j; ++lb) {
             float s[QB];
-            float vv[QB][DB][16];
+            typename E::vec4 vv[QB][DB][4];
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
                 s[qb] = 0.f;
 #pragma unroll
-                for (int t = 0; t < DC; ++t)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) s[qb] = fmaf(to_f32<T>(qf[qb][t][e]), to_f32<T>(dk[qb][t][e]), s[qb]);
+                for (int t = 0; t < DC; ++t) s[qb] = dot8(qf[qb][t], dk[qb][t], s[qb]);
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) vv[qb][db][i] = to_f32<T>(dv[qb][db][i / 4][i % 4]);
+                    for (int i4 = 0; i4 < 4; ++i4) vv[qb][db][i4] = dv[qb][db][i4];
             }
             if (lb < j) request(lb + 1);
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
                 const float sc = half_sum(s[qb]);
-                const float m_new = fmaxf(m[qb], sc);
-                const float alpha = fast_exp2((m[qb] - m_new) * c);   // first key: exp2(-inf) = 0
-                const float p = fast_exp2((sc - m_new) * c);
-                l[qb] = l[qb] * alpha + 0.5f * p;   // the two lane halves are added at the end
-                m[qb] = m_new;
+                const bool grow = (sc - m[qb]) * c > kLazy;   // always for the first key (m = -inf)
+                if (__any(grow)) {
+                    const float m_new = grow ? sc : m[qb];
+                    const float alpha = grow ? fast_exp2((m[qb] - m_new) * c) : 1.f;
+                    m[qb] = m_new;
+                    l[qb] *= alpha;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
+                }
+                const float p = fast_exp2((sc - m[qb]) * c);
+                l[qb] += 0.5f * p;   // the two lane halves are added at the end
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) oacc[qb][db][i] = fmaf(p, vv[qb][db][i], oacc[qb][db][i] * alpha);
+                    for (int i = 0; i < 16; ++i)
+                        oacc[qb][db][i] = fmaf(p, to_f32<T>(vv[qb][db][i / 4][i % 4]), oacc[qb][db][i]);
             }
         }
     }
