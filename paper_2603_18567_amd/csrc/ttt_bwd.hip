@@ -508,6 +508,272 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_kernel(const BwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// dK_0, dV_0: key-stationary, software-pipelined (16-bit element types)
+//
+// Same work split as ttt_bwd_dkv_kernel, but a query tile has 128 rows = 4 blocks of 32 and the
+// blocks are pipelined inside the wave: while the vector ALU turns the scores of block b into
+// P and dS (one element after every matrix instruction), the matrix core accumulates dV, dK of
+// block b-1; operand fragments are requested from LDS a few instructions ahead of their use.
+// LDS: two stages of [Q tile | dO tile] (the stage bit is bit 16 of the per-lane addresses, so all
+// other offsets are immediates) followed by two stages of the per-row vectors LSE, D, doc start.
+// ------------------------------------------------------------------------------------------------
+template <typename T, int D, int NW>
+__global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_pipe_kernel(const BwdArgs a) {
+    static_assert(sizeof(T) == 2, "pipelined dK/dV kernel is for 16-bit elements");
+    using E = Elem<T>;
+    using frag = typename E::frag;
+    using TL = Tile<T, D>;
+    constexpr int KVT = NW * 32;
+    constexpr int QTL = 128;
+    constexpr int NB = QTL / 32;
+    constexpr int DC = D / 16;
+    constexpr int DB = D / 32;
+    constexpr int NT = NW * 64;
+    constexpr int TILE_BYTES = QTL * D * E::kBytes;
+    constexpr int STAGE_BYTES = 1 << 16;
+    static_assert(2 * TILE_BYTES <= STAGE_BYTES, "stage layout");
+    constexpr int VEC_BASE = 2 * STAGE_BYTES;
+    constexpr int VEC_STAGE = 3 * QTL * 4;
+    constexpr int NE = 4 * DB;   // matrix instructions of one dV/dK block update
+    constexpr int PDR = 3;       // row-wise fragment pairs requested ahead
+    constexpr int PDT = 4;       // transposed fragments requested ahead
+    typedef __attribute__((address_space(3))) char lds_char;
+
+    extern __shared__ __align__(16) char smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
+
+    const Geometry& geo = a.geo;
+    int g, rest;
+    if (!decode_block(a.map, blockIdx.x, g, rest)) return;
+    const int sp = rest % a.n_split;
+    const int tile = rest / a.n_split;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, hh = lane >> 5;
+    const int Tn = geo.T;
+    const int kv_tile0 = tile * KVT;
+    const int wk0 = kv_tile0 + wave * 32;
+    const bool active = wk0 < Tn;
+    const int wk_hi = min(wk0 + 31, Tn - 1);
+    const int q_end = __builtin_amdgcn_readfirstlane(a.tok_end[min(kv_tile0 + KVT - 1, Tn - 1)]);
+    const int wq_end = active ? __builtin_amdgcn_readfirstlane(a.tok_end[wk_hi]) : 0;
+    // the wave's 32 keys straddle a document start: some of them are hidden from every later row
+    const bool wave_split = active && __builtin_amdgcn_readfirstlane(a.tok_start[wk_hi]) > wk0;
+    const int qt_lo = kv_tile0 / QTL;
+    const int qt_hi = (q_end - 1) / QTL;
+    const int nqt = qt_hi - qt_lo + 1;
+    const int n_jh = geo.n_steps * geo.G;
+    const int n_c = (n_jh - sp + a.n_split - 1) / a.n_split;
+    const int n_it = n_c * nqt;
+
+    const T* K0 = static_cast<const T*>(a.k[0]) + (int64_t)g * geo.kv_sh;
+    const T* V0 = static_cast<const T*>(a.v[0]) + (int64_t)g * geo.kv_sh;
+    const int kc = min(wk0 + n, Tn - 1);
+    const int kvi = wk0 + n;
+    frag kf[DC], vf[DC];
+#pragma unroll
+    for (int t = 0; t < DC; ++t) {
+        kf[t] = gload_frag<T>(K0 + (int64_t)kc * geo.kv_st + t * 16 + hh * 8);
+        vf[t] = gload_frag<T>(V0 + (int64_t)kc * geo.kv_st + t * 16 + hh * 8);
+    }
+    f32x16 dkacc[DB], dvacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dkacc[db][i] = dvacc[db][i] = 0.f;
+    const float c = geo.scale_log2;
+
+    // per-lane LDS addresses inside stage 0; the stage is toggled by flipping bit 16
+    uint32_t ra[DC], ta[DB][2];
+    {
+        LaneFrags<T, D> lf;
+        lf.init(lane);
+#pragma unroll
+        for (int t = 0; t < DC; ++t) ra[t] = lds0 + lf.row[t];
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            ta[db][0] = lds0 + lf.tr[db][0];
+            ta[db][1] = lds0 + lf.tr[db][1];
+        }
+    }
+    uint32_t va = lds0 + VEC_BASE + hh * 16;   // this lane half's rows inside a group of 8: 4*hh .. +3
+
+    auto ld_row = [&](int which, int qb, int t) -> frag {   // which: 0 = Q tile, 1 = dO tile
+        return *reinterpret_cast<const __attribute__((address_space(3))) frag*>(
+            (uintptr_t)(ra[t] + which * TILE_BYTES + qb * 32 * TL::kRowBytes));
+    };
+    auto ld_tr = [&](int which, int qb, int c2, int db) -> frag {
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        const uint32_t off = which * TILE_BYTES + (qb * 32 + c2 * 16) * TL::kRowBytes;
+        union { s16x4 s[2]; frag v; } u;
+        u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][0] + off));
+        u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][1] + off));
+        return u.v;
+    };
+    auto ld_vec = [&](int which, int qb, int i4) -> f32x4 {   // which: 0 LSE*log2e, 1 D, 2 doc start
+        return *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(
+            (uintptr_t)(va + which * QTL * 4 + (qb * 32 + i4 * 8) * 4));
+    };
+
+    auto issue = [&](int it, int s) {
+        const int ci = it / nqt, qt = qt_lo + it % nqt;
+        const int jh = sp + ci * a.n_split;
+        const int js = jh / geo.G, h = g * geo.G + jh % geo.G;
+        const int j = geo.step_begin + js;
+        const T* Qj = static_cast<const T*>(a.q[j]) + (int64_t)h * geo.q_sh;
+        const T* dOj = static_cast<const T*>(a.d_o[j]) + (int64_t)h * geo.q_sh;
+        char* st = smem + s * STAGE_BYTES;
+        tile_load_async<T, D, QTL, NT>(st, Qj, geo.q_st, qt * QTL, Tn - 1, tid);
+        tile_load_async<T, D, QTL, NT>(st + TILE_BYTES, dOj, geo.q_st, qt * QTL, Tn - 1, tid);
+        if (tid < QTL) {
+            const int q = qt * QTL + tid;
+            const bool in = q < Tn;
+            const int qq = in ? q : Tn - 1;
+            float* vec = reinterpret_cast<float*>(smem + VEC_BASE + s * VEC_STAGE);
+            vec[tid] = in ? a.lse[j][(int64_t)h * Tn + qq] * kLog2e : INFINITY;   // rows past the end: p = 0
+            vec[QTL + tid] = in ? a.delta[((int64_t)js * geo.hq + h) * Tn + qq] : 0.f;
+            reinterpret_cast<int*>(vec)[2 * QTL + tid] = a.tok_start[qq];
+        }
+    };
+
+    if (n_it > 0) issue(0, 0);
+    int stage = 0;
+    for (int it = 0; it < n_it; ++it) {
+        wait_async_copies();
+        __syncthreads();
+        if (it + 1 < n_it) issue(it + 1, stage ^ 1);
+        const int q0 = (qt_lo + it % nqt) * QTL;
+        if (active && q0 + QTL - 1 >= wk0 && q0 < wq_end) {
+            frag qa[DC], ga[DC];         // row-wise Q / dO fragments of the block being scored
+            frag tfr[NE];                // transposed dO / Q fragments of the block being accumulated
+            frag pfr[2], sfr[2];         // P^T and dS^T operands of the previous block
+            f32x16 sacc, pacc;
+
+            auto prime_rows = [&](int qb) {
+#pragma unroll
+                for (int t = 0; t < PDR; ++t) {
+                    qa[t] = ld_row(0, qb, t);
+                    ga[t] = ld_row(1, qb, t);
+                }
+            };
+            // transposed fragment x of block qb: x = (c2 * DB + db) * 2 + (0: dO for dV, 1: Q for dK)
+            auto ld_tfr = [&](int qb, int x) -> frag { return ld_tr(1 - (x & 1), qb, (x >> 1) / DB, (x >> 1) % DB); };
+
+            // scores of block qb: S[q, kv] = Q K^T and dP[q, kv] = dO V^T (lane = kv column)
+            auto score = [&](int qb) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[i] = pacc[i] = 0.f;
+#pragma unroll
+                for (int t = 0; t < DC; ++t) {
+                    if (t + PDR < DC) {
+                        qa[t + PDR] = ld_row(0, qb, t + PDR);
+                        ga[t + PDR] = ld_row(1, qb, t + PDR);
+                    }
+                    issue_fence();
+                    sacc = mma(qa[t], kf[t], sacc);
+                    pacc = mma(ga[t], vf[t], pacc);
+                }
+            };
+
+            // vector work of block qb (P and dS in place of the scores) interleaved, one element per
+            // matrix instruction, with the dV / dK update of block qb - 1
+            auto fused = [&](auto do_c, auto do_e, auto masked, int qb) {
+                constexpr bool DO_C = decltype(do_c)::value != 0;
+                constexpr bool DO_E = decltype(do_e)::value != 0;
+                constexpr bool MASK = decltype(masked)::value != 0;
+                const int eb = DO_C ? qb - 1 : qb;   // block whose dV/dK update runs here
+                if constexpr (DO_E) {
+#pragma unroll
+                    for (int x = 0; x < PDT; ++x) tfr[x] = ld_tfr(eb, x);
+                }
+                f32x4 l4, d4, s4;
+#pragma unroll
+                for (int x = 0; x < 16; ++x) {
+                    if constexpr (DO_E) {
+                        if (x + PDT < NE) tfr[x + PDT] = ld_tfr(eb, x + PDT);
+                    }
+                    if constexpr (DO_C) {
+                        if (x % 4 == 0) {
+                            l4 = ld_vec(0, qb, x / 4);
+                            d4 = ld_vec(1, qb, x / 4);
+                            if constexpr (MASK) s4 = ld_vec(2, qb, x / 4);
+                        }
+                    }
+                    issue_fence();
+                    if constexpr (DO_E) {
+                        if (x < NE) {
+                            const int c2 = (x >> 1) / DB, db = (x >> 1) % DB;
+                            if (x & 1) dkacc[db] = mma(sfr[c2], tfr[x], dkacc[db]);
+                            else       dvacc[db] = mma(pfr[c2], tfr[x], dvacc[db]);
+                        }
+                    }
+                    if constexpr (DO_C) {
+                        float p = fast_exp2(fmaf(sacc[x], c, -l4[x % 4]));
+                        if constexpr (MASK) {
+                            const int q = q0 + qb * 32 + acc_row(x, hh);
+                            p = (kvi <= q && kvi >= __float_as_int(s4[x % 4])) ? p : 0.f;
+                        }
+                        sacc[x] = p;                             // P
+                        pacc[x] = p * (pacc[x] - d4[x % 4]);     // dS
+                    }
+                }
+                issue_fence();
+                if constexpr (DO_C) {
+#pragma unroll
+                    for (int c2 = 0; c2 < 2; ++c2) {
+                        pfr[c2] = acc_chunk<T>(sacc, c2);
+                        sfr[c2] = acc_chunk<T>(pacc, c2);
+                    }
+                }
+            };
+
+            prime_rows(0);
+#pragma unroll
+            for (int qb = 0; qb < NB; ++qb) {
+                score(qb);
+                if (qb + 1 < NB) prime_rows(qb + 1);
+                const int qb0 = q0 + qb * 32;
+                // every row of the block sees every key of the wave iff the block lies at or below the
+                // wave's last key, ends before that key's document does, and the wave's keys are all
+                // in one document
+                const bool need_mask = qb0 < wk0 + 31 || qb0 + 31 >= wq_end || wave_split;
+                if (qb == 0) {
+                    if (need_mask) fused(IntC<1>{}, IntC<0>{}, IntC<1>{}, qb);
+                    else fused(IntC<1>{}, IntC<0>{}, IntC<0>{}, qb);
+                } else {
+                    if (need_mask) fused(IntC<1>{}, IntC<1>{}, IntC<1>{}, qb);
+                    else fused(IntC<1>{}, IntC<1>{}, IntC<0>{}, qb);
+                }
+            }
+            fused(IntC<0>{}, IntC<1>{}, IntC<0>{}, NB - 1);
+        }
+        // next stage
+#pragma unroll
+        for (int t = 0; t < DC; ++t) ra[t] ^= STAGE_BYTES;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            ta[db][0] ^= STAGE_BYTES;
+            ta[db][1] ^= STAGE_BYTES;
+        }
+        va = stage ? va - VEC_STAGE : va + VEC_STAGE;
+        stage ^= 1;
+    }
+    if (!active) return;
+
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int kv = wk0 + acc_row(i, hh);
+            if (kv < Tn) {
+                const int64_t off = ((int64_t)kv * geo.hkv + g) * D + db * 32 + n;
+                atomicAdd(a.dk0_acc + off, dkacc[db][i]);
+                atomicAdd(a.dv0_acc + off, dvacc[db][i]);
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------------------
 // small helpers: clear the block-0 accumulators; convert them to the output dtype
 // ------------------------------------------------------------------------------------------------
 __global__ void ttt_fill_zero_kernel(f32x4* __restrict__ p, int64_t n4) {
@@ -612,11 +878,14 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
     // 4. dK_0, dV_0
     {
         constexpr int KVT = NW_KV * 32;
-        constexpr int LDS = 2 * (2 * 64 * D * (int)sizeof(T) + 3 * 64 * 4);
-        auto kern = ttt_bwd_dkv_kernel<T, D, NW_KV>;
+        constexpr bool kPipe = sizeof(T) == 2;
+        constexpr int LDS = kPipe ? 2 * (1 << 16) + 2 * 3 * 128 * 4 : 2 * (2 * 64 * D * (int)sizeof(T) + 3 * 64 * 4);
+        const void* kern;
+        if constexpr (kPipe) kern = (const void*)ttt_bwd_dkv_pipe_kernel<T, D, NW_KV>;
+        else kern = (const void*)ttt_bwd_dkv_kernel<T, D, NW_KV>;
         static bool attr_done = false;
         if (!attr_done) {
-            e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+            e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
             if (e != hipSuccess) return e;
             attr_done = true;
         }
@@ -631,7 +900,10 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
         {
             ProfileScope prof("ttt_bwd_dkv_kernel", stream);
-            hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW_KV * 64), LDS, stream, a);
+            if constexpr (kPipe)
+                hipLaunchKernelGGL((ttt_bwd_dkv_pipe_kernel<T, D, NW_KV>), dim3((unsigned)grid), dim3(NW_KV * 64), LDS, stream, a);
+            else
+                hipLaunchKernelGGL((ttt_bwd_dkv_kernel<T, D, NW_KV>), dim3((unsigned)grid), dim3(NW_KV * 64), LDS, stream, a);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
