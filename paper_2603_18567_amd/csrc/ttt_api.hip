@@ -67,7 +67,7 @@ int check_ptr(const void* p, const char* what, int step) {
 }
 
 struct Layout {
-    size_t tok_start, tok_end, delta, dk0, dv0, dkl, dvl, total;
+    size_t tok_start, tok_end, delta, lse2, dk0, dv0, dkl, dvl, total;
 };
 
 Layout make_layout(const ttt_attn_params* p, int pass) {
@@ -79,6 +79,7 @@ Layout make_layout(const ttt_attn_params* p, int pass) {
     if (pass != TTT_PASS_FWD) {
         const size_t kv = T * (size_t)p->hkv * (size_t)p->head_dim * sizeof(float);
         L.delta = off; off += align256((size_t)p->k * p->hq * T * sizeof(float));
+        L.lse2 = off;  off += align256((size_t)p->k * p->hq * T * sizeof(float));
         L.dk0 = off;   off += align256(kv);
         L.dv0 = off;   off += align256(kv);
         if (pass == TTT_PASS_BWD_ACCUM) {
@@ -299,6 +300,7 @@ int ttt_attn_bwd(const ttt_attn_params* p, const void* const* q, const void* con
     a.tok_start = tok_start;
     a.tok_end = tok_end;
     a.delta = reinterpret_cast<float*>(ws + L.delta);
+    a.lse2 = reinterpret_cast<float*>(ws + L.lse2);
     a.dk0_acc = reinterpret_cast<float*>(ws + L.dk0);
     a.dv0_acc = reinterpret_cast<float*>(ws + L.dv0);
     a.accumulate = accumulate_dkv;

@@ -47,6 +47,7 @@ struct BwdArgs {
     const int* tok_start;   // [T]
     const int* tok_end;     // [T] one past the last token of each token's document
     float* delta;           // [n_steps][hq][T]  D = <dO, O>
+    float* lse2;            // [n_steps][hq][T]  LSE * log2(e), the exponent offset the kernels use
     float* dk0_acc;         // [T][hkv][d] fp32, block-0 partial sums (atomics)
     float* dv0_acc;
     float* dkl_acc;         // [k-1][T][hkv][d] fp32 carry for blocks l>=1 (accumulate mode), else null

@@ -56,7 +56,11 @@ __global__ __launch_bounds__(256) void ttt_bwd_pre_kernel(const BwdArgs a) {
             d = group_sum<LPR>(d);
             if (sub == 0) {
                 myD[js * G + hg] = d;
-                if (valid) a.delta[((int64_t)js * geo.hq + h) * Tn + i] = d;
+                if (valid) {
+                    const int64_t at = ((int64_t)js * geo.hq + h) * Tn + i;
+                    a.delta[at] = d;
+                    a.lse2[at] = a.lse[j][(int64_t)h * Tn + i] * kLog2e;
+                }
             }
         }
     }
@@ -545,8 +549,10 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_pipe_kernel(const BwdArgs
     const Geometry& geo = a.geo;
     int g, rest;
     if (!decode_block(a.map, blockIdx.x, g, rest)) return;
-    const int sp = rest % a.n_split;
-    const int tile = rest / a.n_split;
+    // workgroups that run at the same time on one XCD share the split, i.e. the same (step, head)
+    // streams of Q and dO, which then stay in that XCD's L2
+    const int sp = rest / a.n_tiles;
+    const int tile = rest % a.n_tiles;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, hh = lane >> 5;
@@ -626,13 +632,17 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_pipe_kernel(const BwdArgs
         tile_load_async<T, D, QTL, NT>(st, Qj, geo.q_st, qt * QTL, Tn - 1, tid);
         tile_load_async<T, D, QTL, NT>(st + TILE_BYTES, dOj, geo.q_st, qt * QTL, Tn - 1, tid);
         if (tid < QTL) {
-            const int q = qt * QTL + tid;
-            const bool in = q < Tn;
-            const int qq = in ? q : Tn - 1;
-            float* vec = reinterpret_cast<float*>(smem + VEC_BASE + s * VEC_STAGE);
-            vec[tid] = in ? a.lse[j][(int64_t)h * Tn + qq] * kLog2e : INFINITY;   // rows past the end: p = 0
-            vec[QTL + tid] = in ? a.delta[((int64_t)js * geo.hq + h) * Tn + qq] : 0.f;
-            reinterpret_cast<int*>(vec)[2 * QTL + tid] = a.tok_start[qq];
+            // per-row vectors ride the same asynchronous path (4 bytes per lane): nothing in this loop
+            // waits for global memory except the copy barrier at its top.  Rows past the end are
+            // clamped; the masked variant hides them.
+            const int qq = min(qt * QTL + tid, Tn - 1);
+            const int64_t at = ((int64_t)js * geo.hq + h) * Tn + qq;
+            char* vec = smem + VEC_BASE + s * VEC_STAGE + (tid & ~63) * 4;   // wave-uniform destination
+            typedef __attribute__((address_space(3))) void lds_void;
+            typedef const __attribute__((address_space(1))) void glb_void;
+            __builtin_amdgcn_global_load_lds((glb_void*)(a.lse2 + at), (lds_void*)(uintptr_t)vec, 4, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_void*)(a.delta + at), (lds_void*)(uintptr_t)(vec + QTL * 4), 4, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_void*)(a.tok_start + qq), (lds_void*)(uintptr_t)(vec + 2 * QTL * 4), 4, 0, 0);
         }
     };
 
@@ -711,7 +721,7 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_pipe_kernel(const BwdArgs
                         float p = fast_exp2(fmaf(sacc[x], c, -l4[x % 4]));
                         if constexpr (MASK) {
                             const int q = q0 + qb * 32 + acc_row(x, hh);
-                            p = (kvi <= q && kvi >= __float_as_int(s4[x % 4])) ? p : 0.f;
+                            p = (kvi <= q && q < wq_end && kvi >= __float_as_int(s4[x % 4])) ? p : 0.f;
                         }
                         sacc[x] = p;                             // P
                         pacc[x] = p * (pacc[x] - d4[x % 4]);     // dS
