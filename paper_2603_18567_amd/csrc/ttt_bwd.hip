@@ -321,6 +321,268 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_kernel(const BwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// dQ: query-stationary, software-pipelined (16-bit element types)
+//
+// One wave = 32 query rows with Q and dO as stationary B operands; a kv tile has 128 rows = 4
+// blocks of 32.  While the vector ALU turns the scores of block b into dS^T (two elements after
+// every matrix instruction), the matrix core accumulates dQ^T += K^T dS^T of block b-1.
+// LDS: two stages of [K tile | V tile]; the stage bit is bit 16 of the per-lane addresses.
+// ------------------------------------------------------------------------------------------------
+template <typename T, int D, int NW>
+__global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs a) {
+    static_assert(sizeof(T) == 2, "pipelined dQ kernel is for 16-bit elements");
+    using E = Elem<T>;
+    using frag = typename E::frag;
+    using TL = Tile<T, D>;
+    constexpr int KT = 128;
+    constexpr int NB = KT / 32;
+    constexpr int QT = NW * 32;
+    constexpr int DC = D / 16;
+    constexpr int DB = D / 32;
+    constexpr int NT = NW * 64;
+    constexpr int TILE_BYTES = KT * D * E::kBytes;
+    constexpr int STAGE_BYTES = 1 << 16;
+    static_assert(2 * TILE_BYTES <= STAGE_BYTES, "stage layout");
+    constexpr int NE = 2 * DB;   // matrix instructions of one dQ block update
+    constexpr int PDR = 3;
+    constexpr int PDT = 4 < NE ? 4 : NE;
+    typedef __attribute__((address_space(3))) char lds_char;
+
+    extern __shared__ __align__(16) char smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
+
+    const Geometry& geo = a.geo;
+    int g, rest;
+    if (!decode_block(a.map, blockIdx.x, g, rest)) return;
+    const int hg = rest % geo.G;
+    rest /= geo.G;
+    const int js = rest % geo.n_steps;
+    const int j = geo.step_begin + js;
+    const int tile = a.n_tiles - 1 - rest / geo.n_steps;
+    const int h = g * geo.G + hg;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, hh = lane >> 5;
+    const int Tn = geo.T;
+    const int q_tile0 = tile * QT;
+    const int wq0 = q_tile0 + wave * 32;
+    const bool active = wq0 < Tn;
+
+    const T* Qj = static_cast<const T*>(a.q[j]) + (int64_t)h * geo.q_sh;
+    const T* dOj = static_cast<const T*>(a.d_o[j]) + (int64_t)h * geo.q_sh;
+    const T* K0 = static_cast<const T*>(a.k[0]) + (int64_t)g * geo.kv_sh;
+    const T* V0 = static_cast<const T*>(a.v[0]) + (int64_t)g * geo.kv_sh;
+
+    const int qi = wq0 + n;
+    const int qc = qi < Tn ? qi : Tn - 1;
+    const int st = a.tok_start[qc];
+    const int64_t at = ((int64_t)js * geo.hq + h) * Tn + qc;
+    const float lse2 = a.lse2[at];
+    const float dl = a.delta[at];
+    const int hi_w = min(wq0 + 31, Tn - 1);
+    const int lo_w = active ? __builtin_amdgcn_readfirstlane(a.tok_start[min(wq0, Tn - 1)]) : 0;
+    const int st_hi = active ? __builtin_amdgcn_readfirstlane(a.tok_start[hi_w]) : 0;
+    const int lo = __builtin_amdgcn_readfirstlane(a.tok_start[q_tile0]);
+    const int hi = min(q_tile0 + QT - 1, Tn - 1);
+    const int u_lo = lo / KT, u_hi = hi / KT;
+
+    frag qf[DC], gof[DC];
+#pragma unroll
+    for (int t = 0; t < DC; ++t) {
+        qf[t] = gload_frag<T>(Qj + (int64_t)qc * geo.q_st + t * 16 + hh * 8);
+        gof[t] = gload_frag<T>(dOj + (int64_t)qc * geo.q_st + t * 16 + hh * 8);
+    }
+    f32x16 dqacc[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dqacc[db][i] = 0.f;
+    const float c = geo.scale_log2;
+
+    uint32_t ra[DC], ta[DB][2];
+    {
+        LaneFrags<T, D> lf;
+        lf.init(lane);
+#pragma unroll
+        for (int t = 0; t < DC; ++t) ra[t] = lds0 + lf.row[t];
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            ta[db][0] = lds0 + lf.tr[db][0];
+            ta[db][1] = lds0 + lf.tr[db][1];
+        }
+    }
+    auto ld_row = [&](int which, int kb, int t) -> frag {   // which: 0 = K tile, 1 = V tile
+        return *reinterpret_cast<const __attribute__((address_space(3))) frag*>(
+            (uintptr_t)(ra[t] + which * TILE_BYTES + kb * 32 * TL::kRowBytes));
+    };
+    auto ld_ktr = [&](int kb, int x) -> frag {   // K^T fragment x = c2 * DB + db of block kb
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        const int c2 = x / DB, db = x % DB;
+        const uint32_t off = (kb * 32 + c2 * 16) * TL::kRowBytes;
+        union { s16x4 s[2]; frag v; } u;
+        u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][0] + off));
+        u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][1] + off));
+        return u.v;
+    };
+    auto issue = [&](int u, int s) {
+        char* stg = smem + s * STAGE_BYTES;
+        tile_load_async<T, D, KT, NT>(stg, K0, geo.kv_st, u * KT, Tn - 1, tid);
+        tile_load_async<T, D, KT, NT>(stg + TILE_BYTES, V0, geo.kv_st, u * KT, Tn - 1, tid);
+    };
+
+    issue(u_lo, 0);
+    int stage = 0;
+    for (int u = u_lo; u <= u_hi; ++u) {
+        wait_async_copies();
+        __syncthreads();
+        if (u < u_hi) issue(u + 1, stage ^ 1);
+        const int kv0 = u * KT;
+        if (active && kv0 <= hi_w && kv0 + KT - 1 >= lo_w) {
+            frag ka[DC], va[DC];   // row-wise K / V fragments of the block being scored
+            frag tfr[NE];          // K^T fragments of the block being accumulated
+            frag sfr[2];           // dS^T operands of the previous block
+            f32x16 sacc, pacc;
+            auto prime_rows = [&](int kb) {
+#pragma unroll
+                for (int t = 0; t < PDR; ++t) {
+                    ka[t] = ld_row(0, kb, t);
+                    va[t] = ld_row(1, kb, t);
+                }
+            };
+            // S^T[kv, q] = K Q^T and dP^T[kv, q] = V dO^T (lane = query row)
+            auto score = [&](int kb) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[i] = pacc[i] = 0.f;
+#pragma unroll
+                for (int t = 0; t < DC; ++t) {
+                    if (t + PDR < DC) {
+                        ka[t + PDR] = ld_row(0, kb, t + PDR);
+                        va[t + PDR] = ld_row(1, kb, t + PDR);
+                    }
+                    issue_fence();
+                    sacc = mma(ka[t], qf[t], sacc);
+                    pacc = mma(va[t], gof[t], pacc);
+                }
+            };
+            auto fused = [&](auto do_c, auto do_e, auto masked, int kb) {
+                constexpr bool DO_C = decltype(do_c)::value != 0;
+                constexpr bool DO_E = decltype(do_e)::value != 0;
+                constexpr bool MASK = decltype(masked)::value != 0;
+                const int eb = DO_C ? kb - 1 : kb;
+                if constexpr (DO_E) {
+#pragma unroll
+                    for (int x = 0; x < PDT; ++x) tfr[x] = ld_ktr(eb, x);
+                }
+                constexpr int GS = 2;            // matrix instructions per group
+                constexpr int NG = NE / GS;      // groups
+                constexpr int EPG = 16 / NG;     // elements per group
+#pragma unroll
+                for (int y = 0; y < NG; ++y) {
+                    if constexpr (DO_E) {
+#pragma unroll
+                        for (int x = GS * y + PDT; x < GS * y + PDT + GS; ++x)
+                            if (x < NE) tfr[x] = ld_ktr(eb, x);
+                    }
+                    issue_fence();
+                    if constexpr (DO_E) {
+#pragma unroll
+                        for (int x = GS * y; x < GS * y + GS; ++x) dqacc[x % DB] = mma(tfr[x], sfr[x / DB], dqacc[x % DB]);
+                    }
+                    if constexpr (DO_C) {
+#pragma unroll
+                        for (int x = EPG * y; x < EPG * y + EPG; ++x) {
+                            float p = fast_exp2(fmaf(sacc[x], c, -lse2));
+                            if constexpr (MASK) {
+                                const int kv = kv0 + kb * 32 + acc_row(x, hh);
+                                p = (kv <= qi && kv >= st) ? p : 0.f;
+                            }
+                            pacc[x] = p * (pacc[x] - dl);   // dS^T
+                        }
+                    }
+                }
+                issue_fence();
+                if constexpr (DO_C) {
+                    sfr[0] = acc_chunk<T>(pacc, 0);
+                    sfr[1] = acc_chunk<T>(pacc, 1);
+                }
+            };
+
+            prime_rows(0);
+#pragma unroll
+            for (int kb = 0; kb < NB; ++kb) {
+                score(kb);
+                if (kb + 1 < NB) prime_rows(kb + 1);
+                const int kb0 = kv0 + kb * 32;
+                const bool need_mask = kb0 + 31 > wq0 || kb0 < st_hi;
+                if (kb == 0) {
+                    if (need_mask) fused(IntC<1>{}, IntC<0>{}, IntC<1>{}, kb);
+                    else fused(IntC<1>{}, IntC<0>{}, IntC<0>{}, kb);
+                } else {
+                    if (need_mask) fused(IntC<1>{}, IntC<1>{}, IntC<1>{}, kb);
+                    else fused(IntC<1>{}, IntC<1>{}, IntC<0>{}, kb);
+                }
+            }
+            fused(IntC<0>{}, IntC<1>{}, IntC<0>{}, NB - 1);
+        }
+#pragma unroll
+        for (int t = 0; t < DC; ++t) ra[t] ^= STAGE_BYTES;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            ta[db][0] ^= STAGE_BYTES;
+            ta[db][1] ^= STAGE_BYTES;
+        }
+        stage ^= 1;
+    }
+    __syncthreads();   // everybody is done with the tile stages: they become the store patches
+    if (!active) return;
+
+    // diagonal keys of blocks 1..j
+    for (int lb = 1; lb <= j; ++lb) {
+        const T* krow = static_cast<const T*>(a.k[lb]) + (int64_t)g * geo.kv_sh + (int64_t)qc * geo.kv_st;
+        const T* vrow = static_cast<const T*>(a.v[lb]) + (int64_t)g * geo.kv_sh + (int64_t)qc * geo.kv_st;
+        float s = 0.f, dp = 0.f;
+#pragma unroll
+        for (int t = 0; t < DC; ++t) {
+            s = dot8(qf[t], gload_frag<T>(krow + t * 16 + hh * 8), s);
+            dp = dot8(gof[t], gload_frag<T>(vrow + t * 16 + hh * 8), dp);
+        }
+        s = half_sum(s);
+        dp = half_sum(dp);
+        const float p = fast_exp2(fmaf(s, c, -lse2));
+        const float ds = p * (dp - dl);
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const typename E::vec4 kk = gload_vec4<T>(krow + db * 32 + i4 * 8 + hh * 4);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) dqacc[db][i4 * 4 + x] = fmaf(ds, to_f32<T>(kk[x]), dqacc[db][i4 * 4 + x]);
+            }
+    }
+
+    // scaled rows go through a wave-private LDS patch so that global stores are whole 16-byte pieces
+    char* patch = smem + wave * (32 * D * E::kBytes);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            typename E::vec4 pk;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) pk[x] = (T)(dqacc[db][i4 * 4 + x] * geo.scale);
+            *reinterpret_cast<typename E::vec4*>(patch + TL::offset(n, db * 32 + i4 * 8 + hh * 4)) = pk;
+        }
+    T* obase = static_cast<T*>(a.dq[j]) + (int64_t)h * geo.q_sh;
+#pragma unroll
+    for (int it = 0; it < 32 * TL::kPieces / 64; ++it) {
+        const int pidx = it * 64 + lane;
+        const int r = pidx / TL::kPieces, piece = pidx % TL::kPieces;
+        const int row = wq0 + r;
+        const f32x4 val = *reinterpret_cast<const f32x4*>(patch + r * TL::kRowBytes + ((piece ^ TL::swz(r)) * 16));
+        if (row < Tn) *reinterpret_cast<f32x4*>(obase + (int64_t)row * geo.q_st + piece * TL::kElemsPerPiece) = val;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // dK_0, dV_0: key-stationary
 // ------------------------------------------------------------------------------------------------
 template <typename T, int D, int NW>
@@ -696,35 +958,57 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_pipe_kernel(const BwdArgs
 #pragma unroll
                     for (int x = 0; x < PDT; ++x) tfr[x] = ld_tfr(eb, x);
                 }
-                f32x4 l4, d4, s4;
+                // groups of four: the operands of group y+1 (transposed fragments, per-row vectors) are
+                // requested before group y is worked on; inside a group the four matrix instructions
+                // alternate with the vector instructions of four independent elements
+                f32x4 l4[2], d4[2], s4[2];
+                if constexpr (DO_C) {
+                    l4[0] = ld_vec(0, qb, 0);
+                    d4[0] = ld_vec(1, qb, 0);
+                    if constexpr (MASK) s4[0] = ld_vec(2, qb, 0);
+                }
 #pragma unroll
-                for (int x = 0; x < 16; ++x) {
+                for (int y = 0; y < 4; ++y) {
                     if constexpr (DO_E) {
-                        if (x + PDT < NE) tfr[x + PDT] = ld_tfr(eb, x + PDT);
+#pragma unroll
+                        for (int x = 4 * y + PDT; x < 4 * y + PDT + 4; ++x)
+                            if (x < NE) tfr[x] = ld_tfr(eb, x);
                     }
                     if constexpr (DO_C) {
-                        if (x % 4 == 0) {
-                            l4 = ld_vec(0, qb, x / 4);
-                            d4 = ld_vec(1, qb, x / 4);
-                            if constexpr (MASK) s4 = ld_vec(2, qb, x / 4);
+                        if (y + 1 < 4) {
+                            l4[(y + 1) & 1] = ld_vec(0, qb, y + 1);
+                            d4[(y + 1) & 1] = ld_vec(1, qb, y + 1);
+                            if constexpr (MASK) s4[(y + 1) & 1] = ld_vec(2, qb, y + 1);
                         }
                     }
                     issue_fence();
-                    if constexpr (DO_E) {
-                        if (x < NE) {
-                            const int c2 = (x >> 1) / DB, db = (x >> 1) % DB;
-                            if (x & 1) dkacc[db] = mma(sfr[c2], tfr[x], dkacc[db]);
-                            else       dvacc[db] = mma(pfr[c2], tfr[x], dvacc[db]);
+#pragma unroll
+                    for (int x = 4 * y; x < 4 * y + 4; ++x) {
+                        if constexpr (DO_E) {
+                            if (x < NE) {
+                                const int c2 = (x >> 1) / DB, db = (x >> 1) % DB;
+                                if (x & 1) dkacc[db] = mma(sfr[c2], tfr[x], dkacc[db]);
+                                else       dvacc[db] = mma(pfr[c2], tfr[x], dvacc[db]);
+                            }
+                        }
+                        if constexpr (DO_C) {
+                            float p = fast_exp2(fmaf(sacc[x], c, -l4[y & 1][x % 4]));
+                            if constexpr (MASK) {
+                                const int q = q0 + qb * 32 + acc_row(x, hh);
+                                p = (kvi <= q && q < wq_end && kvi >= __float_as_int(s4[y & 1][x % 4])) ? p : 0.f;
+                            }
+                            sacc[x] = p;                                 // P
+                            pacc[x] = p * (pacc[x] - d4[y & 1][x % 4]);   // dS
                         }
                     }
-                    if constexpr (DO_C) {
-                        float p = fast_exp2(fmaf(sacc[x], c, -l4[x % 4]));
-                        if constexpr (MASK) {
-                            const int q = q0 + qb * 32 + acc_row(x, hh);
-                            p = (kvi <= q && q < wq_end && kvi >= __float_as_int(s4[x % 4])) ? p : 0.f;
+                    if constexpr (DO_C && DO_E) {
+                        // one matrix instruction, then the vector work of one element, four times
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x002, MASK ? 8 : 3, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
                         }
-                        sacc[x] = p;                             // P
-                        pacc[x] = p * (pacc[x] - d4[x % 4]);     // dS
                     }
                 }
                 issue_fence();
@@ -865,12 +1149,16 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
 
     // 3. dQ
     {
-        constexpr int QT = NW_DQ * QB_DQ * 32;
-        constexpr int LDS = 4 * 64 * D * (int)sizeof(T);
-        auto kern = ttt_bwd_dq_kernel<T, D, QB_DQ, NW_DQ>;
+        constexpr bool kPipe = sizeof(T) == 2;
+        constexpr int NWQ = kPipe ? 4 : NW_DQ;
+        constexpr int QT = NWQ * (kPipe ? 1 : QB_DQ) * 32;
+        constexpr int LDS = kPipe ? 2 * (1 << 16) : 4 * 64 * D * (int)sizeof(T);
+        const void* kern;
+        if constexpr (kPipe) kern = (const void*)ttt_bwd_dq_pipe_kernel<T, D, NWQ>;
+        else kern = (const void*)ttt_bwd_dq_kernel<T, D, QB_DQ, NW_DQ>;
         static bool attr_done = false;
         if (!attr_done) {
-            e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+            e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
             if (e != hipSuccess) return e;
             attr_done = true;
         }
@@ -880,7 +1168,10 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
         {
             ProfileScope prof("ttt_bwd_dq_kernel", stream);
-            hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW_DQ * 64), LDS, stream, a);
+            if constexpr (kPipe)
+                hipLaunchKernelGGL((ttt_bwd_dq_pipe_kernel<T, D, NWQ>), dim3((unsigned)grid), dim3(NWQ * 64), LDS, stream, a);
+            else
+                hipLaunchKernelGGL((ttt_bwd_dq_kernel<T, D, QB_DQ, NW_DQ>), dim3((unsigned)grid), dim3(NW_DQ * 64), LDS, stream, a);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
