@@ -536,28 +536,38 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
     __syncthreads();   // everybody is done with the tile stages: they become the store patches
     if (!active) return;
 
-    // diagonal keys of blocks 1..j
-    for (int lb = 1; lb <= j; ++lb) {
-        const T* krow = static_cast<const T*>(a.k[lb]) + (int64_t)g * geo.kv_sh + (int64_t)qc * geo.kv_st;
-        const T* vrow = static_cast<const T*>(a.v[lb]) + (int64_t)g * geo.kv_sh + (int64_t)qc * geo.kv_st;
-        float s = 0.f, dp = 0.f;
+    // diagonal keys of blocks 1..j; the rows of block lb+1 are requested before block lb is consumed
+    if (j >= 1) {
+        frag dk[DC], dv[DC];
+        auto request = [&](int lb) {
+            const T* krow = static_cast<const T*>(a.k[lb]) + (int64_t)g * geo.kv_sh + (int64_t)qc * geo.kv_st;
+            const T* vrow = static_cast<const T*>(a.v[lb]) + (int64_t)g * geo.kv_sh + (int64_t)qc * geo.kv_st;
 #pragma unroll
-        for (int t = 0; t < DC; ++t) {
-            s = dot8(qf[t], gload_frag<T>(krow + t * 16 + hh * 8), s);
-            dp = dot8(gof[t], gload_frag<T>(vrow + t * 16 + hh * 8), dp);
-        }
-        s = half_sum(s);
-        dp = half_sum(dp);
-        const float p = fast_exp2(fmaf(s, c, -lse2));
-        const float ds = p * (dp - dl);
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const typename E::vec4 kk = gload_vec4<T>(krow + db * 32 + i4 * 8 + hh * 4);
-#pragma unroll
-                for (int x = 0; x < 4; ++x) dqacc[db][i4 * 4 + x] = fmaf(ds, to_f32<T>(kk[x]), dqacc[db][i4 * 4 + x]);
+            for (int t = 0; t < DC; ++t) {
+                dk[t] = gload_frag<T>(krow + t * 16 + hh * 8);
+                dv[t] = gload_frag<T>(vrow + t * 16 + hh * 8);
             }
+        };
+        request(1);
+        for (int lb = 1; lb <= j; ++lb) {
+            float s = 0.f, dp = 0.f;
+            float kk[DB][16];   // the key row in accumulator order
+#pragma unroll
+            for (int t = 0; t < DC; ++t) {
+                s = dot8(qf[t], dk[t], s);
+                dp = dot8(gof[t], dv[t], dp);
+            }
+            frags_to_acc_order<T, DC>(dk, kk);
+            if (lb < j) request(lb + 1);
+            s = half_sum(s);
+            dp = half_sum(dp);
+            const float p = fast_exp2(fmaf(s, c, -lse2));
+            const float ds = p * (dp - dl);
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) dqacc[db][i] = fmaf(ds, kk[db][i], dqacc[db][i]);
+        }
     }
 
     // scaled rows go through a wave-private LDS patch so that global stores are whole 16-byte pieces

@@ -271,6 +271,33 @@ TTT_DEV float dot8(const f32x8& a, const f32x8& b, float acc) {
     return acc;
 }
 
+// Row-wise fragments of ONE row per lane pair (lane (n,hh) holds elements 16t + 8hh + e of row n)
+// -> the accumulator-column order (lane (n,hh) holds elements 32db + 8*i4 + 4hh + x), as fp32.
+// Each lane keeps half of its own values and takes the other half from its partner lane n +- 32;
+// one v_permlane32_swap per register pair moves both directions at once.
+template <typename T, int DC> TTT_DEV void frags_to_acc_order(const typename Elem<T>::frag (&f)[DC], float (&out)[DC / 2][16]) {
+    constexpr int R = sizeof(typename Elem<T>::frag) / 4;   // 32-bit registers per fragment
+    union U { typename Elem<T>::frag v; uint32_t r[R]; };
+#pragma unroll
+    for (int t = 0; t < DC; ++t) {
+        U u;
+        u.v = f[t];
+        union { uint32_t r[R / 2]; T e[4]; } even, odd;
+#pragma unroll
+        for (int i = 0; i < R / 2; ++i) {
+            const auto sw = __builtin_amdgcn_permlane32_swap(u.r[i], u.r[i + R / 2], false, false);
+            even.r[i] = sw[0];   // half 0: own first half,       half 1: partner's second half
+            odd.r[i] = sw[1];    // half 0: partner's first half, half 1: own second half
+        }
+        const int db = t / 2, i4 = 2 * (t % 2);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            out[db][i4 * 4 + x] = to_f32<T>(even.e[x]);
+            out[db][(i4 + 1) * 4 + x] = to_f32<T>(odd.e[x]);
+        }
+    }
+}
+
 // load 8 consecutive elements from global as a fragment
 template <typename T> TTT_DEV typename Elem<T>::frag gload_frag(const T* p);
 template <> TTT_DEV bf16x8 gload_frag<__bf16>(const __bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }

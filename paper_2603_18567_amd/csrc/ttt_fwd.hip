@@ -193,8 +193,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
     // so that their global-memory latency overlaps the first tile copy.  Row-wise dot products on
     // the vector ALU; the fragments of block lb+1 are requested before block lb is consumed.
     if (active && j >= 1) {
-        frag dk[QB][DC];
-        typename E::vec4 dv[QB][DB][4];
+        frag dk[QB][DC], dv[QB][DC];
         auto request = [&](int lb) {
             const T* Kl = static_cast<const T*>(a.k[lb]) + (int64_t)g * geo.kv_sh;
             const T* Vl = static_cast<const T*>(a.v[lb]) + (int64_t)g * geo.kv_sh;
@@ -203,26 +202,22 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
                 const T* krow = Kl + (int64_t)qc[qb] * geo.kv_st;
                 const T* vrow = Vl + (int64_t)qc[qb] * geo.kv_st;
 #pragma unroll
-                for (int t = 0; t < DC; ++t) dk[qb][t] = gload_frag<T>(krow + t * 16 + hh * 8);
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int i4 = 0; i4 < 4; ++i4) dv[qb][db][i4] = gload_vec4<T>(vrow + db * 32 + i4 * 8 + hh * 4);
+                for (int t = 0; t < DC; ++t) {
+                    dk[qb][t] = gload_frag<T>(krow + t * 16 + hh * 8);
+                    dv[qb][t] = gload_frag<T>(vrow + t * 16 + hh * 8);
+                }
             }
         };
         request(1);
         for (int lb = 1; lb <= j; ++lb) {
             float s[QB];
-            typename E::vec4 vv[QB][DB][4];
+            float vv[QB][DB][16];   // the key's value row in accumulator order
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
                 s[qb] = 0.f;
 #pragma unroll
                 for (int t = 0; t < DC; ++t) s[qb] = dot8(qf[qb][t], dk[qb][t], s[qb]);
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int i4 = 0; i4 < 4; ++i4) vv[qb][db][i4] = dv[qb][db][i4];
+                frags_to_acc_order<T, DC>(dv[qb], vv[qb]);
             }
             if (lb < j) request(lb + 1);
 #pragma unroll
@@ -244,8 +239,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        oacc[qb][db][i] = fmaf(p, to_f32<T>(vv[qb][db][i / 4][i % 4]), oacc[qb][db][i]);
+                    for (int i = 0; i < 16; ++i) oacc[qb][db][i] = fmaf(p, vv[qb][db][i], oacc[qb][db][i]);
             }
         }
     }
