@@ -30,36 +30,46 @@ def parse():
     ap.add_argument("--workload", default="headline_4k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of the oracle sample (0 = sized for ~15 s)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
-def cpu_baseline(wl, inp, rows_override=0):
+def cpu_baseline(wl, inp, rows_override=0, target_s=15.0):
     """The fp64 oracle, as it stands, on a seeded sample of query rows of this workload
-    (forward + backward restricted to those rows = a row-sparse cotangent)."""
+    (forward + backward restricted to those rows = a row-sparse cotangent).  A short pilot sizes
+    the sample for about `target_s` seconds on this host."""
     import numpy as np
     import torch
     import oracle
     oracle.build_oracle()
     cores = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
     rng = np.random.default_rng(wl.seed)
-    # ~4e6 visible (pair x head) per second on 8 cores was measured for this oracle; aim at ~15 s
-    mean_pairs_per_row = wl.pairs() / (wl.k * wl.T)
-    n_rows = rows_override or int(max(8, min(wl.k * wl.T, 4.0e6 * cores / 8 * 15 / mean_pairs_per_row)))
-    rs = rng.integers(0, wl.k, n_rows).astype(np.int32)
-    rt = rng.integers(0, wl.T, n_rows).astype(np.int32)
     f32 = lambda ts: np.stack([t.to(torch.float32).numpy() for t in ts])
     Q, K, V = f32(inp.q), f32(inp.k), f32(inp.v)
-    dO_rows = np.stack([inp.d_o[j][i].to(torch.float32).numpy() for j, i in zip(rs, rt)])
     cu = np.asarray(wl.cu_seqlens)
-    starts = cu[np.searchsorted(cu, rt, side="right") - 1]
-    pairs = int(((rt - starts + 1) + rs).sum()) * wl.hq
-    t0 = time.perf_counter()
-    oracle.oracle_run(Q, K, V, wl.cu_seqlens, wl.scale, rs, rt, dO_rows)
-    dt = time.perf_counter() - t0
+
+    def run(n_rows):
+        rs = rng.integers(0, wl.k, n_rows).astype(np.int32)
+        rt = rng.integers(0, wl.T, n_rows).astype(np.int32)
+        dO_rows = np.stack([inp.d_o[j][i].to(torch.float32).numpy() for j, i in zip(rs, rt)])
+        starts = cu[np.searchsorted(cu, rt, side="right") - 1]
+        pairs = int(((rt - starts + 1) + rs).sum()) * wl.hq
+        t0 = time.perf_counter()
+        oracle.oracle_run(Q, K, V, wl.cu_seqlens, wl.scale, rs, rt, dO_rows)
+        return pairs, time.perf_counter() - t0
+
+    if rows_override:
+        n_rows = rows_override
+    else:
+        p_pairs, p_dt = run(4 * cores)                      # pilot
+        rows_per_s = 4 * cores / max(p_dt, 1e-3)
+        n_rows = int(max(4 * cores, min(wl.k * wl.T, rows_per_s * target_s)))
+    pairs, dt = run(n_rows)
     flops = 14 * wl.d * pairs
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "sample": f"{n_rows} seeded query rows (all {wl.hq} heads) of {wl.name}: fwd+bwd of those rows, "
-                      f"{pairs:.3e} visible pairs in {dt:.1f} s; full workload would take ~{wl.pairs() / pairs * dt:.0f} s (extrapolated)"}
+                      f"{pairs:.3e} visible pairs in {dt:.1f} s; the full workload would take ~{wl.pairs() / pairs * dt:.0f} s (extrapolated)"}
 
 
 def main():
@@ -90,6 +100,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.full((256 << 20,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # timed region: K steps between two synchronisations; per-call events for the fwd/bwd split and
     # per-kernel events (library diagnostics) for the roofline of the dominant kernel
