@@ -5,11 +5,13 @@
 //   ttt_bwd_pre_kernel   D for every (step, head, token); and the complete dK_l, dV_l of the later
 //                        cache blocks l >= 1, which are only ever read on the diagonal (suffix part
 //                        of Alg. 2), so one small group of lanes owns each (token, kv head) -- no atomics.
-//   ttt_bwd_dq_kernel    query-stationary, same streaming structure as the forward: dQ_j.
+//   ttt_bwd_dq_kernel    query-stationary, same streaming structure as the forward: dQ_j
+//                        (ttt_bwd_dq_pipe_kernel: block-pipelined variant for 16-bit types).
 //   ttt_bwd_dkv_kernel   key-stationary over block 0: each wave keeps 32 rows of K_0, V_0 as
 //                        operands and their dK, dV accumulators in registers while every
 //                        (step, head of the group, query tile at or below the diagonal) streams past
-//                        through LDS; partial sums of the (step, head) splits meet in fp32 atomics.
+//                        through LDS; partial sums of the (step, head) splits meet in fp32 atomics
+//                        (ttt_bwd_dkv_ws_kernel: wave-specialised variant for 16-bit types).
 //   ttt_bwd_finish_kernel  fp32 block-0 sums -> dK_0, dV_0 in the tensor dtype.
 #include "ttt_args.hpp"
 
@@ -784,84 +786,72 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_kernel(const BwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// dK_0, dV_0: key-stationary, software-pipelined (16-bit element types)
+// dK_0, dV_0: key-stationary, wave-specialised (16-bit element types)
 //
-// Same work split as ttt_bwd_dkv_kernel, but a query tile has 128 rows = 4 blocks of 32 and the
-// blocks are pipelined inside the wave: while the vector ALU turns the scores of block b into
-// P and dS (one element after every matrix instruction), the matrix core accumulates dV, dK of
-// block b-1; operand fragments are requested from LDS a few instructions ahead of their use.
-// LDS: two stages of [Q tile | dO tile] (the stage bit is bit 16 of the per-lane addresses, so all
-// other offsets are immediates) followed by two stages of the per-row vectors LSE, D, doc start.
+// Measured on MI355X: vector instructions issued by the wave that also issues the matrix
+// instructions mostly serialise with them, while vector instructions of a SECOND wave on the same
+// SIMD hide in the matrix instructions' shadow.  So the eight waves of a workgroup form four pairs
+// (wave w and wave w+4 share a SIMD), each pair owning 32 key rows:
+//   score wave  (w):   S = Q K^T, dP = dO V^T for one 32-row query block (K_0, V_0 rows stationary
+//                      in registers), then P and dS on the vector ALU, written to LDS as ready-made
+//                      operand fragments;
+//   update wave (w+4): one block behind, reads those fragments and the transposed dO / Q fragments
+//                      and accumulates dV += P^T dO, dK += dS^T Q (accumulators in registers).
+// Both roles issue 16 matrix instructions per block; one workgroup barrier per block hands the
+// fragments over.  Query tiles of 64 rows rotate through three LDS stages; a copy is requested two
+// blocks before its first use.
 // ------------------------------------------------------------------------------------------------
-template <typename T, int D, int NW>
-__global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_pipe_kernel(const BwdArgs a) {
-    static_assert(sizeof(T) == 2, "pipelined dK/dV kernel is for 16-bit elements");
+template <typename T, int D>
+__device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const int g, const int sp, const int tile) {
+    static_assert(sizeof(T) == 2, "wave-specialised dK/dV kernel is for 16-bit elements");
     using E = Elem<T>;
     using frag = typename E::frag;
     using TL = Tile<T, D>;
-    constexpr int KVT = NW * 32;
-    constexpr int QTL = 128;
-    constexpr int NB = QTL / 32;
+    constexpr int KVT = 128;                  // 4 pairs x 32 key rows
+    constexpr int QTL = 64;                   // query rows per LDS tile = 2 blocks
     constexpr int DC = D / 16;
     constexpr int DB = D / 32;
-    constexpr int NT = NW * 64;
+    constexpr int NT = 512;
+    constexpr int NS = 3;                     // LDS stages
     constexpr int TILE_BYTES = QTL * D * E::kBytes;
-    constexpr int STAGE_BYTES = 1 << 16;
-    static_assert(2 * TILE_BYTES <= STAGE_BYTES, "stage layout");
-    constexpr int VEC_BASE = 2 * STAGE_BYTES;
+    constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+    constexpr int VEC_BASE = NS * STAGE_BYTES;
     constexpr int VEC_STAGE = 3 * QTL * 4;
-    constexpr int NE = 4 * DB;   // matrix instructions of one dV/dK block update
-    constexpr int PDR = 3;       // row-wise fragment pairs requested ahead
-    constexpr int PDT = 4;       // transposed fragments requested ahead
+    constexpr int X_BASE = (VEC_BASE + NS * VEC_STAGE + 1023) & ~1023;
+    constexpr int X_SLOT = 4 * 1024;          // P^T (2 chunks) and dS^T (2 chunks), 1 KiB per fragment
+    constexpr int NE = 4 * DB;
+    // LDS latency under load is several hundred cycles here, far more than a few matrix
+    // instructions: every fragment of a block is requested before its first matrix instruction
+    constexpr int PDR = DC;
+    constexpr int PDT = NE;
     typedef __attribute__((address_space(3))) char lds_char;
 
-    extern __shared__ __align__(16) char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
-
     const Geometry& geo = a.geo;
-    int g, rest;
-    if (!decode_block(a.map, blockIdx.x, g, rest)) return;
-    // workgroups that run at the same time on one XCD share the split, i.e. the same (step, head)
-    // streams of Q and dO, which then stay in that XCD's L2
-    const int sp = rest / a.n_tiles;
-    const int tile = rest % a.n_tiles;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int role = wave >> 2;               // 0: score wave, 1: update wave
+    const int pair = wave & 3;
     const int n = lane & 31, hh = lane >> 5;
     const int Tn = geo.T;
     const int kv_tile0 = tile * KVT;
-    const int wk0 = kv_tile0 + wave * 32;
+    const int wk0 = kv_tile0 + pair * 32;
     const bool active = wk0 < Tn;
     const int wk_hi = min(wk0 + 31, Tn - 1);
     const int q_end = __builtin_amdgcn_readfirstlane(a.tok_end[min(kv_tile0 + KVT - 1, Tn - 1)]);
     const int wq_end = active ? __builtin_amdgcn_readfirstlane(a.tok_end[wk_hi]) : 0;
-    // the wave's 32 keys straddle a document start: some of them are hidden from every later row
     const bool wave_split = active && __builtin_amdgcn_readfirstlane(a.tok_start[wk_hi]) > wk0;
     const int qt_lo = kv_tile0 / QTL;
     const int qt_hi = (q_end - 1) / QTL;
     const int nqt = qt_hi - qt_lo + 1;
     const int n_jh = geo.n_steps * geo.G;
     const int n_c = (n_jh - sp + a.n_split - 1) / a.n_split;
-    const int n_it = n_c * nqt;
-
-    const T* K0 = static_cast<const T*>(a.k[0]) + (int64_t)g * geo.kv_sh;
-    const T* V0 = static_cast<const T*>(a.v[0]) + (int64_t)g * geo.kv_sh;
-    const int kc = min(wk0 + n, Tn - 1);
-    const int kvi = wk0 + n;
-    frag kf[DC], vf[DC];
-#pragma unroll
-    for (int t = 0; t < DC; ++t) {
-        kf[t] = gload_frag<T>(K0 + (int64_t)kc * geo.kv_st + t * 16 + hh * 8);
-        vf[t] = gload_frag<T>(V0 + (int64_t)kc * geo.kv_st + t * 16 + hh * 8);
-    }
-    f32x16 dkacc[DB], dvacc[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) dkacc[db][i] = dvacc[db][i] = 0.f;
+    const int n_it = n_c * nqt;               // query tiles this workgroup streams
+    const int n_blk = 2 * n_it;
     const float c = geo.scale_log2;
+    const int kvi = wk0 + n;
 
-    // per-lane LDS addresses inside stage 0; the stage is toggled by flipping bit 16
+    // per-lane LDS addresses inside stage 0
     uint32_t ra[DC], ta[DB][2];
     {
         LaneFrags<T, D> lf;
@@ -874,196 +864,248 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_pipe_kernel(const BwdArgs
             ta[db][1] = lds0 + lf.tr[db][1];
         }
     }
-    uint32_t va = lds0 + VEC_BASE + hh * 16;   // this lane half's rows inside a group of 8: 4*hh .. +3
+    const uint32_t xa = lds0 + X_BASE + pair * (2 * X_SLOT) + lane * 16;   // this lane's place in slot 0
+    const uint32_t va0 = lds0 + VEC_BASE + hh * 16;
 
-    auto ld_row = [&](int which, int qb, int t) -> frag {   // which: 0 = Q tile, 1 = dO tile
+    auto ld_row = [&](uint32_t sb, int which, int qb, int t) -> frag {
         return *reinterpret_cast<const __attribute__((address_space(3))) frag*>(
-            (uintptr_t)(ra[t] + which * TILE_BYTES + qb * 32 * TL::kRowBytes));
+            (uintptr_t)(ra[t] + sb + which * TILE_BYTES + qb * 32 * TL::kRowBytes));
     };
-    auto ld_tr = [&](int which, int qb, int c2, int db) -> frag {
+    auto ld_tr = [&](uint32_t sb, int which, int qb, int c2, int db) -> frag {
         typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-        const uint32_t off = which * TILE_BYTES + (qb * 32 + c2 * 16) * TL::kRowBytes;
+        const uint32_t off = sb + which * TILE_BYTES + (qb * 32 + c2 * 16) * TL::kRowBytes;
         union { s16x4 s[2]; frag v; } u;
         u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][0] + off));
         u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][1] + off));
         return u.v;
     };
-    auto ld_vec = [&](int which, int qb, int i4) -> f32x4 {   // which: 0 LSE*log2e, 1 D, 2 doc start
+    auto ld_vec = [&](uint32_t vb, int which, int qb, int i4) -> f32x4 {
         return *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(
-            (uintptr_t)(va + which * QTL * 4 + (qb * 32 + i4 * 8) * 4));
+            (uintptr_t)(va0 + vb + which * QTL * 4 + (qb * 32 + i4 * 8) * 4));
     };
 
-    auto issue = [&](int it, int s) {
-        const int ci = it / nqt, qt = qt_lo + it % nqt;
-        const int jh = sp + ci * a.n_split;
+    // Copy source of this thread inside a query tile, computed once: NLD pieces of the Q tile and of
+    // the dO tile per thread (same positions in both).  Only a tile that reaches past the last token
+    // needs its rows clamped.
+    constexpr int NLD = QTL * TL::kPieces / NT;
+    static_assert(2 * NLD + 3 <= 15, "partial vmcnt wait must fit the 4 low counter bits");
+    int64_t src_off[NLD];   // element offset of the piece inside the tile (token stride applied)
+    int src_row[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int pidx = (i * (NT / 64) + wave) * 64 + lane;
+        const int r = pidx / TL::kPieces, pos = pidx % TL::kPieces;
+        src_row[i] = r;
+        src_off[i] = (int64_t)r * geo.q_st + ((pos ^ TL::swz(r)) * TL::kElemsPerPiece);
+    }
+    // tile counter -> (step/head pair, query tile, LDS stage), advanced without divisions
+    int is_ci = 0, is_qt = qt_lo, is_stage = 0;
+    auto issue_next = [&]() {
+        const int jh = sp + is_ci * a.n_split;
         const int js = jh / geo.G, h = g * geo.G + jh % geo.G;
         const int j = geo.step_begin + js;
         const T* Qj = static_cast<const T*>(a.q[j]) + (int64_t)h * geo.q_sh;
         const T* dOj = static_cast<const T*>(a.d_o[j]) + (int64_t)h * geo.q_sh;
-        char* st = smem + s * STAGE_BYTES;
-        tile_load_async<T, D, QTL, NT>(st, Qj, geo.q_st, qt * QTL, Tn - 1, tid);
-        tile_load_async<T, D, QTL, NT>(st + TILE_BYTES, dOj, geo.q_st, qt * QTL, Tn - 1, tid);
+        char* st = smem + is_stage * STAGE_BYTES;
+        const int row0 = is_qt * QTL;
+        typedef __attribute__((address_space(3))) void lds_void;
+        typedef const __attribute__((address_space(1))) void glb_void;
+        if (row0 + QTL <= Tn) {
+            const T* qb = Qj + (int64_t)row0 * geo.q_st;
+            const T* gb = dOj + (int64_t)row0 * geo.q_st;
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                const int base = (i * (NT / 64) + wave) * 64 * 16;
+                __builtin_amdgcn_global_load_lds((glb_void*)(qb + src_off[i]), (lds_void*)(uintptr_t)(st + base), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((glb_void*)(gb + src_off[i]), (lds_void*)(uintptr_t)(st + TILE_BYTES + base), 16, 0, 0);
+            }
+        } else {
+            tile_load_async<T, D, QTL, NT>(st, Qj, geo.q_st, row0, Tn - 1, tid);
+            tile_load_async<T, D, QTL, NT>(st + TILE_BYTES, dOj, geo.q_st, row0, Tn - 1, tid);
+        }
         if (tid < QTL) {
-            // per-row vectors ride the same asynchronous path (4 bytes per lane): nothing in this loop
-            // waits for global memory except the copy barrier at its top.  Rows past the end are
-            // clamped; the masked variant hides them.
-            const int qq = min(qt * QTL + tid, Tn - 1);
+            const int qq = min(row0 + tid, Tn - 1);
             const int64_t at = ((int64_t)js * geo.hq + h) * Tn + qq;
-            char* vec = smem + VEC_BASE + s * VEC_STAGE + (tid & ~63) * 4;   // wave-uniform destination
-            typedef __attribute__((address_space(3))) void lds_void;
-            typedef const __attribute__((address_space(1))) void glb_void;
+            char* vec = smem + VEC_BASE + is_stage * VEC_STAGE;
             __builtin_amdgcn_global_load_lds((glb_void*)(a.lse2 + at), (lds_void*)(uintptr_t)vec, 4, 0, 0);
             __builtin_amdgcn_global_load_lds((glb_void*)(a.delta + at), (lds_void*)(uintptr_t)(vec + QTL * 4), 4, 0, 0);
             __builtin_amdgcn_global_load_lds((glb_void*)(a.tok_start + qq), (lds_void*)(uintptr_t)(vec + 2 * QTL * 4), 4, 0, 0);
         }
+        if (++is_stage == NS) is_stage = 0;
+        if (++is_qt == qt_lo + nqt) {
+            is_qt = qt_lo;
+            ++is_ci;
+        }
     };
 
-    if (n_it > 0) issue(0, 0);
-    int stage = 0;
-    for (int it = 0; it < n_it; ++it) {
-        wait_async_copies();
-        __syncthreads();
-        if (it + 1 < n_it) issue(it + 1, stage ^ 1);
-        const int q0 = (qt_lo + it % nqt) * QTL;
-        if (active && q0 + QTL - 1 >= wk0 && q0 < wq_end) {
-            frag qa[DC], ga[DC];         // row-wise Q / dO fragments of the block being scored
-            frag tfr[NE];                // transposed dO / Q fragments of the block being accumulated
-            frag pfr[2], sfr[2];         // P^T and dS^T operands of the previous block
-            f32x16 sacc, pacc;
+    // Walks the block sequence without divisions: block b lives in tile b/2, LDS stage (b/2) % NS,
+    // query tile qt_lo + (b/2) % nqt.
+    struct Cursor {
+        int stage, qt, qb;   // LDS stage, query tile index, block inside the tile
+        __device__ void next(int nqt_, int qt_lo_) {
+            if (++qb == 2) {
+                qb = 0;
+                if (++stage == NS) stage = 0;
+                if (++qt == qt_lo_ + nqt_) qt = qt_lo_;
+            }
+        }
+    };
+    auto visible = [&](const Cursor& cur) {
+        const int q0 = cur.qt * QTL + cur.qb * 32;
+        return active && q0 + 31 >= wk0 && q0 < wq_end;
+    };
+    // common to both roles at the top of step s: tile s/2 + 2 goes into the stage that the update
+    // waves left at the end of step s - 1
+    // Copies, common to both roles.  At the top of an odd step s, tile s/2 + 2 is requested into the
+    // stage that the update waves left at the end of step s - 1; at the bottom of that step, before
+    // its barrier, the wave waits until only those newest requests are outstanding, i.e. until
+    // tile s/2 + 1 (needed from step s + 1 on, requested two steps ago) has landed.
+    auto step_copies_top = [&](int s) -> bool {
+        if ((s & 1) && (s >> 1) + 2 < n_it) {
+            issue_next();
+            return true;
+        }
+        return false;
+    };
+    auto step_copies_bottom = [&](int s, bool issued) {
+        if (!(s & 1) || (s >> 1) + 1 >= n_it) return;
+        if (!issued) {
+            wait_async_copies();
+        } else if (wave == 0) {
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * NLD + 3));   // vmcnt = this wave's newest requests
+        } else {
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * NLD));
+        }
+    };
 
-            auto prime_rows = [&](int qb) {
+    if (n_it > 0) issue_next();
+    if (n_it > 1) issue_next();
+    wait_async_copies();
+    __syncthreads();
+
+    // The two roles run separate loops with the same number of barriers (n_blk + 1), so that each
+    // role's registers hold only its own state.
+    if (role == 0) {
+        // ---- score waves: K_0, V_0 rows of the pair as stationary B operands
+        frag kf[DC], vf[DC];
+        {
+            const T* K0 = static_cast<const T*>(a.k[0]) + (int64_t)g * geo.kv_sh;
+            const T* V0 = static_cast<const T*>(a.v[0]) + (int64_t)g * geo.kv_sh;
+            const int kc = min(wk0 + n, Tn - 1);
+#pragma unroll
+            for (int t = 0; t < DC; ++t) {
+                kf[t] = gload_frag<T>(K0 + (int64_t)kc * geo.kv_st + t * 16 + hh * 8);
+                vf[t] = gload_frag<T>(V0 + (int64_t)kc * geo.kv_st + t * 16 + hh * 8);
+            }
+        }
+        __builtin_amdgcn_s_setprio(2);   // the score waves' matrix instructions go first: their vector
+                                         // work then runs while the update waves use the matrix core
+        Cursor cur{0, qt_lo, 0};
+        for (int s = 0; s <= n_blk; ++s, cur.next(nqt, qt_lo)) {
+            const bool issued = step_copies_top(s);
+            if (s < n_blk && visible(cur)) {
+                const int b = s, qb = cur.qb;
+                const uint32_t sb = cur.stage * STAGE_BYTES;
+                const uint32_t vb = cur.stage * VEC_STAGE;
+                const int q0 = cur.qt * QTL + qb * 32;
+                frag qa[DC], ga[DC];
+                f32x16 sacc, pacc;
 #pragma unroll
                 for (int t = 0; t < PDR; ++t) {
-                    qa[t] = ld_row(0, qb, t);
-                    ga[t] = ld_row(1, qb, t);
+                    qa[t] = ld_row(sb, 0, qb, t);
+                    ga[t] = ld_row(sb, 1, qb, t);
                 }
-            };
-            // transposed fragment x of block qb: x = (c2 * DB + db) * 2 + (0: dO for dV, 1: Q for dK)
-            auto ld_tfr = [&](int qb, int x) -> frag { return ld_tr(1 - (x & 1), qb, (x >> 1) / DB, (x >> 1) % DB); };
-
-            // scores of block qb: S[q, kv] = Q K^T and dP[q, kv] = dO V^T (lane = kv column)
-            auto score = [&](int qb) {
+                f32x4 l4[4], d4[4];
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    l4[i4] = ld_vec(vb, 0, qb, i4);
+                    d4[i4] = ld_vec(vb, 1, qb, i4);
+                }
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sacc[i] = pacc[i] = 0.f;
 #pragma unroll
                 for (int t = 0; t < DC; ++t) {
                     if (t + PDR < DC) {
-                        qa[t + PDR] = ld_row(0, qb, t + PDR);
-                        ga[t + PDR] = ld_row(1, qb, t + PDR);
+                        qa[t + PDR] = ld_row(sb, 0, qb, t + PDR);
+                        ga[t + PDR] = ld_row(sb, 1, qb, t + PDR);
                     }
                     issue_fence();
                     sacc = mma(qa[t], kf[t], sacc);
                     pacc = mma(ga[t], vf[t], pacc);
                 }
-            };
-
-            // vector work of block qb (P and dS in place of the scores) interleaved, one element per
-            // matrix instruction, with the dV / dK update of block qb - 1
-            auto fused = [&](auto do_c, auto do_e, auto masked, int qb) {
-                constexpr bool DO_C = decltype(do_c)::value != 0;
-                constexpr bool DO_E = decltype(do_e)::value != 0;
-                constexpr bool MASK = decltype(masked)::value != 0;
-                const int eb = DO_C ? qb - 1 : qb;   // block whose dV/dK update runs here
-                if constexpr (DO_E) {
+                // every row of the block sees every key of the pair iff the block lies at or below
+                // the pair's last key, ends before that key's document does, and the pair's keys are
+                // all in one document
+                const bool need_mask = q0 < wk0 + 31 || q0 + 31 >= wq_end || wave_split;
+                if (need_mask) {
 #pragma unroll
-                    for (int x = 0; x < PDT; ++x) tfr[x] = ld_tfr(eb, x);
-                }
-                // groups of four: the operands of group y+1 (transposed fragments, per-row vectors) are
-                // requested before group y is worked on; inside a group the four matrix instructions
-                // alternate with the vector instructions of four independent elements
-                f32x4 l4[2], d4[2], s4[2];
-                if constexpr (DO_C) {
-                    l4[0] = ld_vec(0, qb, 0);
-                    d4[0] = ld_vec(1, qb, 0);
-                    if constexpr (MASK) s4[0] = ld_vec(2, qb, 0);
-                }
-#pragma unroll
-                for (int y = 0; y < 4; ++y) {
-                    if constexpr (DO_E) {
-#pragma unroll
-                        for (int x = 4 * y + PDT; x < 4 * y + PDT + 4; ++x)
-                            if (x < NE) tfr[x] = ld_tfr(eb, x);
+                    for (int x = 0; x < 16; ++x) {
+                        const f32x4 s4 = ld_vec(vb, 2, qb, x / 4);
+                        const int q = q0 + acc_row(x, hh);
+                        float p = fast_exp2(fmaf(sacc[x], c, -l4[x / 4][x % 4]));
+                        p = (kvi <= q && q < wq_end && kvi >= __float_as_int(s4[x % 4])) ? p : 0.f;
+                        sacc[x] = p;
+                        pacc[x] = p * (pacc[x] - d4[x / 4][x % 4]);
                     }
-                    if constexpr (DO_C) {
-                        if (y + 1 < 4) {
-                            l4[(y + 1) & 1] = ld_vec(0, qb, y + 1);
-                            d4[(y + 1) & 1] = ld_vec(1, qb, y + 1);
-                            if constexpr (MASK) s4[(y + 1) & 1] = ld_vec(2, qb, y + 1);
-                        }
-                    }
-                    issue_fence();
-#pragma unroll
-                    for (int x = 4 * y; x < 4 * y + 4; ++x) {
-                        if constexpr (DO_E) {
-                            if (x < NE) {
-                                const int c2 = (x >> 1) / DB, db = (x >> 1) % DB;
-                                if (x & 1) dkacc[db] = mma(sfr[c2], tfr[x], dkacc[db]);
-                                else       dvacc[db] = mma(pfr[c2], tfr[x], dvacc[db]);
-                            }
-                        }
-                        if constexpr (DO_C) {
-                            float p = fast_exp2(fmaf(sacc[x], c, -l4[y & 1][x % 4]));
-                            if constexpr (MASK) {
-                                const int q = q0 + qb * 32 + acc_row(x, hh);
-                                p = (kvi <= q && q < wq_end && kvi >= __float_as_int(s4[y & 1][x % 4])) ? p : 0.f;
-                            }
-                            sacc[x] = p;                                 // P
-                            pacc[x] = p * (pacc[x] - d4[y & 1][x % 4]);   // dS
-                        }
-                    }
-                    if constexpr (DO_C && DO_E) {
-                        // one matrix instruction, then the vector work of one element, four times
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                            __builtin_amdgcn_sched_group_barrier(0x002, MASK ? 8 : 3, 0);
-                            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
-                        }
-                    }
-                }
-                issue_fence();
-                if constexpr (DO_C) {
-#pragma unroll
-                    for (int c2 = 0; c2 < 2; ++c2) {
-                        pfr[c2] = acc_chunk<T>(sacc, c2);
-                        sfr[c2] = acc_chunk<T>(pacc, c2);
-                    }
-                }
-            };
-
-            prime_rows(0);
-#pragma unroll
-            for (int qb = 0; qb < NB; ++qb) {
-                score(qb);
-                if (qb + 1 < NB) prime_rows(qb + 1);
-                const int qb0 = q0 + qb * 32;
-                // every row of the block sees every key of the wave iff the block lies at or below the
-                // wave's last key, ends before that key's document does, and the wave's keys are all
-                // in one document
-                const bool need_mask = qb0 < wk0 + 31 || qb0 + 31 >= wq_end || wave_split;
-                if (qb == 0) {
-                    if (need_mask) fused(IntC<1>{}, IntC<0>{}, IntC<1>{}, qb);
-                    else fused(IntC<1>{}, IntC<0>{}, IntC<0>{}, qb);
                 } else {
-                    if (need_mask) fused(IntC<1>{}, IntC<1>{}, IntC<1>{}, qb);
-                    else fused(IntC<1>{}, IntC<1>{}, IntC<0>{}, qb);
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) {
+                        const float p = fast_exp2(fmaf(sacc[x], c, -l4[x / 4][x % 4]));
+                        sacc[x] = p;
+                        pacc[x] = p * (pacc[x] - d4[x / 4][x % 4]);
+                    }
+                }
+                // hand P^T and dS^T over as operand fragments
+                const uint32_t xs = xa + (b & 1) * X_SLOT;
+#pragma unroll
+                for (int c2 = 0; c2 < 2; ++c2) {
+                    *reinterpret_cast<__attribute__((address_space(3))) frag*>((uintptr_t)(xs + c2 * 1024)) = acc_chunk<T>(sacc, c2);
+                    *reinterpret_cast<__attribute__((address_space(3))) frag*>((uintptr_t)(xs + (2 + c2) * 1024)) = acc_chunk<T>(pacc, c2);
                 }
             }
-            fused(IntC<0>{}, IntC<1>{}, IntC<0>{}, NB - 1);
+            step_copies_bottom(s, issued);
+            __syncthreads();   // fragments of block s are visible; slot and stage of block s-1 are free
         }
-        // next stage
+        return;
+    }
+
+    // ---- update waves: one block behind
+    f32x16 dkacc[DB], dvacc[DB];
 #pragma unroll
-        for (int t = 0; t < DC; ++t) ra[t] ^= STAGE_BYTES;
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-            ta[db][0] ^= STAGE_BYTES;
-            ta[db][1] ^= STAGE_BYTES;
+        for (int i = 0; i < 16; ++i) dkacc[db][i] = dvacc[db][i] = 0.f;
+    Cursor cur{0, qt_lo, 0};   // block s - 1
+    for (int s = 0; s <= n_blk; ++s) {
+        const bool issued = step_copies_top(s);
+        if (s >= 1 && visible(cur)) {
+            const int b = s - 1, qb = cur.qb;
+            const uint32_t sb = cur.stage * STAGE_BYTES;
+            const uint32_t xs = xa + (b & 1) * X_SLOT;
+            frag pfr[2], sfr[2], tfr[NE];
+#pragma unroll
+            for (int c2 = 0; c2 < 2; ++c2) {
+                pfr[c2] = *reinterpret_cast<const __attribute__((address_space(3))) frag*>((uintptr_t)(xs + c2 * 1024));
+                sfr[c2] = *reinterpret_cast<const __attribute__((address_space(3))) frag*>((uintptr_t)(xs + (2 + c2) * 1024));
+            }
+            // transposed fragment x = (c2 * DB + db) * 2 + (0: dO for dV, 1: Q for dK)
+            auto ld_tfr = [&](int x) -> frag { return ld_tr(sb, 1 - (x & 1), qb, (x >> 1) / DB, (x >> 1) % DB); };
+#pragma unroll
+            for (int x = 0; x < PDT; ++x) tfr[x] = ld_tfr(x);
+#pragma unroll
+            for (int x = 0; x < NE; ++x) {
+                if (x + PDT < NE) tfr[x + PDT] = ld_tfr(x + PDT);
+                issue_fence();
+                const int c2 = (x >> 1) / DB, db = (x >> 1) % DB;
+                if (x & 1) dkacc[db] = mma(sfr[c2], tfr[x], dkacc[db]);
+                else       dvacc[db] = mma(pfr[c2], tfr[x], dvacc[db]);
+            }
         }
-        va = stage ? va - VEC_STAGE : va + VEC_STAGE;
-        stage ^= 1;
+        if (s >= 1) cur.next(nqt, qt_lo);
+        step_copies_bottom(s, issued);
+        __syncthreads();
     }
     if (!active) return;
-
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -1075,6 +1117,26 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_pipe_kernel(const BwdArgs
                 atomicAdd(a.dv0_acc + off, dvacc[db][i]);
             }
         }
+}
+
+// One workgroup takes key tile u and its mirror n_tiles-1-u, one after the other: the two together
+// see the same number of query tiles whatever u is, so all workgroups of a (step, head) split carry
+// equal work, finish together, and the ones resident on an XCD keep streaming the same Q/dO tensors
+// (which then stay in that XCD's L2).
+template <typename T, int D>
+__global__ __launch_bounds__(512) void ttt_bwd_dkv_ws_kernel(const BwdArgs a) {
+    extern __shared__ __align__(16) char smem[];
+    int g, rest;
+    if (!decode_block(a.map, blockIdx.x, g, rest)) return;
+    const int n_half = (a.n_tiles + 1) / 2;
+    const int sp = rest / n_half;
+    const int u = rest % n_half;
+    dkv_ws_tile<T, D>(a, smem, g, sp, u);
+    const int mirror = a.n_tiles - 1 - u;
+    if (mirror != u) {
+        __syncthreads();
+        dkv_ws_tile<T, D>(a, smem, g, sp, mirror);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1188,11 +1250,12 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
 
     // 4. dK_0, dV_0
     {
-        constexpr int KVT = NW_KV * 32;
-        constexpr bool kPipe = sizeof(T) == 2;
-        constexpr int LDS = kPipe ? 2 * (1 << 16) + 2 * 3 * 128 * 4 : 2 * (2 * 64 * D * (int)sizeof(T) + 3 * 64 * 4);
+        constexpr bool kWs = sizeof(T) == 2;      // wave-specialised kernel for 16-bit types
+        constexpr int KVT = kWs ? 128 : NW_KV * 32;
+        constexpr int WS_LDS = ((3 * 2 * 64 * D * 2 + 3 * 3 * 64 * 4 + 1023) & ~1023) + 4 * 2 * 4096;
+        constexpr int LDS = kWs ? WS_LDS : 2 * (2 * 64 * D * (int)sizeof(T) + 3 * 64 * 4);
         const void* kern;
-        if constexpr (kPipe) kern = (const void*)ttt_bwd_dkv_pipe_kernel<T, D, NW_KV>;
+        if constexpr (kWs) kern = (const void*)ttt_bwd_dkv_ws_kernel<T, D>;
         else kern = (const void*)ttt_bwd_dkv_kernel<T, D, NW_KV>;
         static bool attr_done = false;
         if (!attr_done) {
@@ -1204,15 +1267,17 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         // split the (step, head) list of a kv tile so that the grid has a few thousand workgroups
         const int n_jh = geo.n_steps * geo.G;
         int n_split = 1;
-        while (n_split < n_jh && (int64_t)a.n_tiles * geo.hkv * n_split < 2048) ++n_split;
+        // units per kv head and split: key tiles, or mirrored pairs of key tiles
+        const int n_units = kWs ? (a.n_tiles + 1) / 2 : a.n_tiles;
+        while (n_split < n_jh && (int64_t)n_units * geo.hkv * n_split < (kWs ? 1024 : 2048)) ++n_split;
         a.n_split = n_split;
         int64_t grid;
-        set_head_map(a.map, geo.hkv, a.n_tiles * n_split, grid);
+        set_head_map(a.map, geo.hkv, n_units * n_split, grid);
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
         {
             ProfileScope prof("ttt_bwd_dkv_kernel", stream);
-            if constexpr (kPipe)
-                hipLaunchKernelGGL((ttt_bwd_dkv_pipe_kernel<T, D, NW_KV>), dim3((unsigned)grid), dim3(NW_KV * 64), LDS, stream, a);
+            if constexpr (kWs)
+                hipLaunchKernelGGL((ttt_bwd_dkv_ws_kernel<T, D>), dim3((unsigned)grid), dim3(512), LDS, stream, a);
             else
                 hipLaunchKernelGGL((ttt_bwd_dkv_kernel<T, D, NW_KV>), dim3((unsigned)grid), dim3(NW_KV * 64), LDS, stream, a);
         }

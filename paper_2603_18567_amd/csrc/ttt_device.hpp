@@ -75,14 +75,19 @@ template <typename T, int D> struct Tile {
     static constexpr int kRowBytes = D * Elem<T>::kBytes;
     static constexpr int kPieces = kRowBytes / 16;              // 8, 16 or 32
     static constexpr int kElemsPerPiece = 16 / Elem<T>::kBytes;
-    // swz(r): row bits rotated left by one inside the piece-index width.  Four consecutive rows then
-    // differ in piece bits 1..2 (the transposing 8-byte reads of a 16-lane group hit 4 rows x 32 B:
-    // all banks distinct) and 16 consecutive rows still take 16 distinct values (row-wise 16-byte
-    // reads stay conflict-free).  Measured on MI355X: 16-byte reads ~220 B/clk/CU, transposing reads
-    // ~120 B/clk/CU with this map against ~63 with a plain r & 15.
+    // swz(r): the two low row bits go to the top of the piece index, the next two to the bottom.
+    // LDS has 64 banks x 4 B (one 256-byte window).  A transposing 8-byte read serves 32 lanes per
+    // cycle = 4 consecutive rows x 4 pieces x 2 halves: the low row bits move each row to a
+    // different group of 4 pieces, so the 256 bytes are distinct.  A row-wise 16-byte read serves
+    // 16 lanes = 16 consecutive rows per cycle: swz is a bijection of the low four row bits, so the
+    // 16 pieces are distinct.  Measured with SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE on MI355X:
+    // 4.0 cycles per 16-byte read and 2.0 per transposing read, no conflict cycles (a plain row & 15
+    // gives 8 cycles per transposing read, a one-bit rotation 4).
     static constexpr int kBits = kPieces >= 16 ? 4 : 3;
-    static constexpr int kSwzMask = (1 << kBits) - 1;
-    TTT_DEV static int swz(int r) { return ((r << 1) & kSwzMask & ~1) | ((r >> (kBits - 1)) & 1); }
+    TTT_DEV static int swz(int r) {
+        if constexpr (kBits == 4) return ((r & 3) << 2) | ((r >> 2) & 3);
+        else return (((r >> 1) & 1) << 2) | ((r >> 2) & 3);   // 128-byte rows: two rows per bank window
+    }
     // byte offset of element (r, col) inside the tile
     TTT_DEV static int offset(int r, int col) {
         const int piece = col / kElemsPerPiece;
