@@ -129,6 +129,124 @@ __global__ __launch_bounds__(256) void ttt_bwd_pre_kernel(const BwdArgs a) {
     }
 }
 
+// Sum over an aligned group of LPR (4, 8 or 16) lanes with DPP moves only (no LDS traffic):
+// quad butterflies, then the half-row and the row mirror pair up quads and half-rows.
+template <int LPR> TTT_DEV float group_sum_dpp(float v) {
+    auto mv = [](float x, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value, 0xf, 0xf, true));
+    };
+    v += mv(v, IntC<0xB1>{});                              // quad_perm [1,0,3,2]
+    v += mv(v, IntC<0x4E>{});                              // quad_perm [2,3,0,1]
+    if constexpr (LPR >= 8) v += mv(v, IntC<0x141>{});     // row_half_mirror
+    if constexpr (LPR >= 16) v += mv(v, IntC<0x140>{});    // row_mirror
+    return v;
+}
+
+// The same work for 16-bit types and at most KMAX steps, reading every Q_j, dO_j, O_j row exactly
+// once: the K_l, V_l rows of this (token, kv head) and their fp32 gradients stay in registers while
+// one sweep over (step, head of the group) feeds all of them (the diagonal part of Eq. (6)'s
+// backward: key (l, i) is seen only by the queries (j >= l, i)).
+template <typename T, int D, int KMAX>
+__global__ __launch_bounds__(256) void ttt_bwd_pre_regs_kernel(const BwdArgs a) {
+    static_assert(sizeof(T) == 2, "register budget sized for 16-bit elements");
+    using frag = typename Elem<T>::frag;
+    constexpr int LPR = D / 8;
+    constexpr int UPB = 256 / LPR;
+    constexpr int NL = KMAX - 1;
+
+    const Geometry& geo = a.geo;
+    const int Tn = geo.T, G = geo.G, ns = geo.n_steps, b = geo.step_begin, e = b + ns;
+    const int grp = threadIdx.x / LPR, sub = threadIdx.x % LPR;
+    const int64_t unit = (int64_t)blockIdx.x * UPB + grp;
+    if (unit >= (int64_t)Tn * geo.hkv) return;   // whole aligned lane groups leave together
+    const int i = (int)(unit / geo.hkv);
+    const int g = (int)(unit % geo.hkv);
+    const int64_t kvoff = (int64_t)i * geo.kv_st + (int64_t)g * geo.kv_sh + sub * 8;
+
+    frag kf[NL], vf[NL];
+    float dk[NL][8], dv[NL][8];
+#pragma unroll
+    for (int l = 0; l < NL; ++l) {
+        const int lb = l + 1 < e ? l + 1 : 0;     // unused slots read block 0's row (in bounds), never used
+        kf[l] = gload_frag<T>(static_cast<const T*>(a.k[lb]) + kvoff);
+        vf[l] = gload_frag<T>(static_cast<const T*>(a.v[lb]) + kvoff);
+#pragma unroll
+        for (int x = 0; x < 8; ++x) dk[l][x] = dv[l][x] = 0.f;
+    }
+
+    for (int js = 0; js < ns; ++js) {
+        const int j = b + js;
+        for (int hg = 0; hg < G; ++hg) {
+            const int h = g * G + hg;
+            const int64_t off = (int64_t)i * geo.q_st + (int64_t)h * geo.q_sh + sub * 8;
+            const frag qf = gload_frag<T>(static_cast<const T*>(a.q[j]) + off);
+            const frag go = gload_frag<T>(static_cast<const T*>(a.d_o[j]) + off);
+            const frag oo = gload_frag<T>(static_cast<const T*>(a.o[j]) + off);
+            const float lse2 = a.lse[j][(int64_t)h * Tn + i] * kLog2e;
+            const float dsum = group_sum_dpp<LPR>(dot8(go, oo, 0.f));
+            if (sub == 0) {
+                const int64_t at = ((int64_t)js * geo.hq + h) * Tn + i;
+                a.delta[at] = dsum;
+                a.lse2[at] = lse2;
+            }
+            float qx[8], gx[8];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                qx[x] = to_f32<T>(qf[x]);
+                gx[x] = to_f32<T>(go[x]);
+            }
+#pragma unroll
+            for (int l = 0; l < NL; ++l) {
+                if (l + 1 > j) break;              // block l+1 is visible from step j >= l+1 only
+                const float s = group_sum_dpp<LPR>(dot8(qf, kf[l], 0.f));
+                const float dp = group_sum_dpp<LPR>(dot8(go, vf[l], 0.f));
+                const float p = fast_exp2(s * (geo.scale * kLog2e) - lse2);
+                const float ds = p * (dp - dsum) * geo.scale;
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    dk[l][x] = fmaf(ds, qx[x], dk[l][x]);
+                    dv[l][x] = fmaf(p, gx[x], dv[l][x]);
+                }
+            }
+        }
+    }
+
+#pragma unroll
+    for (int l = 0; l < NL; ++l) {
+        const int lb = l + 1;
+        if (lb >= e) break;
+        if (a.accumulate) {
+            // fp32 carry across the calls of a descending-step sweep; this group owns its slice
+            const int64_t coff = (((int64_t)l * Tn + i) * geo.hkv + g) * D + sub * 8;
+            f32x4* ck = reinterpret_cast<f32x4*>(a.dkl_acc + coff);
+            f32x4* cv = reinterpret_cast<f32x4*>(a.dvl_acc + coff);
+            if (!a.carry_reset) {
+#pragma unroll
+                for (int v4 = 0; v4 < 2; ++v4) {
+                    const f32x4 pk = ck[v4], pv = cv[v4];
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        dk[l][4 * v4 + x] += pk[x];
+                        dv[l][4 * v4 + x] += pv[x];
+                    }
+                }
+            }
+#pragma unroll
+            for (int v4 = 0; v4 < 2; ++v4) {
+                ck[v4] = f32x4{dk[l][4 * v4], dk[l][4 * v4 + 1], dk[l][4 * v4 + 2], dk[l][4 * v4 + 3]};
+                cv[v4] = f32x4{dv[l][4 * v4], dv[l][4 * v4 + 1], dv[l][4 * v4 + 2], dv[l][4 * v4 + 3]};
+            }
+            if (lb < b) continue;   // not complete yet: earlier steps' calls have not run
+        }
+        T* gk = static_cast<T*>(a.dk[lb]) + kvoff;
+        T* gv = static_cast<T*>(a.dv[lb]) + kvoff;
+        gstore_vec4<T>(gk, dk[l][0], dk[l][1], dk[l][2], dk[l][3]);
+        gstore_vec4<T>(gk + 4, dk[l][4], dk[l][5], dk[l][6], dk[l][7]);
+        gstore_vec4<T>(gv, dv[l][0], dv[l][1], dv[l][2], dv[l][3]);
+        gstore_vec4<T>(gv + 4, dv[l][4], dv[l][5], dv[l][6], dv[l][7]);
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // dQ: query-stationary
 // ------------------------------------------------------------------------------------------------
@@ -1207,12 +1325,20 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         const int64_t grid = (units + UPB - 1) / UPB;
         const size_t lds = (size_t)UPB * geo.n_steps * geo.G * sizeof(float);
         if (grid > 0x7fffffffLL || lds > 160 * 1024) return hipErrorInvalidValue;
-        auto kern = ttt_bwd_pre_kernel<T, D>;
-        if (lds > 48 * 1024) {
-            e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
-        {
+        constexpr int KREG = 8;   // steps whose diagonal rows and gradients fit the register file
+        bool in_regs = false;
+        if constexpr (sizeof(T) == 2) in_regs = geo.step_begin + geo.n_steps <= KREG;
+        if (in_regs) {
+            if constexpr (sizeof(T) == 2) {
+                ProfileScope prof("ttt_bwd_pre_kernel", stream);
+                hipLaunchKernelGGL((ttt_bwd_pre_regs_kernel<T, D, KREG>), dim3((unsigned)grid), dim3(256), 0, stream, a);
+            }
+        } else {
+            auto kern = ttt_bwd_pre_kernel<T, D>;
+            if (lds > 48 * 1024) {
+                e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                if (e != hipSuccess) return e;
+            }
             ProfileScope prof("ttt_bwd_pre_kernel", stream);
             hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, stream, a);
         }
