@@ -909,16 +909,20 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_kernel(const BwdArgs a) {
 // Measured on MI355X: vector instructions issued by the wave that also issues the matrix
 // instructions mostly serialise with them, while vector instructions of a SECOND wave on the same
 // SIMD hide in the matrix instructions' shadow.  So the eight waves of a workgroup form four pairs
-// (wave w and wave w+4 share a SIMD), each pair owning 32 key rows:
-//   score wave  (w):   S = Q K^T, dP = dO V^T for one 32-row query block (K_0, V_0 rows stationary
-//                      in registers), then P and dS on the vector ALU, written to LDS as ready-made
-//                      operand fragments;
+// (wave w and wave w+4 share a SIMD), each pair owning 32 of the workgroup's 128 key rows:
+//   score wave  (w):   S = Q K^T, dP = dO V^T for one block of 32 query rows (K_0, V_0 rows
+//                      stationary in registers), then P and dS on the vector ALU, written to LDS as
+//                      ready-made operand fragments.  The Q / dO fragments of the NEXT block are
+//                      requested from LDS before the vector work starts, so their latency (several
+//                      hundred cycles under load) is off the critical path;
 //   update wave (w+4): one block behind, reads those fragments and the transposed dO / Q fragments
-//                      and accumulates dV += P^T dO, dK += dS^T Q (accumulators in registers).
+//                      and accumulates dV += P^T dO, dK += dS^T Q (accumulators in registers).  It
+//                      also requests the global -> LDS copies, four blocks ahead: it has the slack.
 // Both roles issue 16 matrix instructions per block; one workgroup barrier per block hands the
-// fragments over.  Query tiles of 64 rows rotate through three LDS stages; a copy is requested two
-// blocks before its first use.
+// fragments over.  Query blocks (Q and dO rows) rotate through six LDS stages.
 // ------------------------------------------------------------------------------------------------
+constexpr int kDkvStages = 6;
+
 template <typename T, int D>
 __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const int g, const int sp, const int tile) {
     static_assert(sizeof(T) == 2, "wave-specialised dK/dV kernel is for 16-bit elements");
@@ -926,28 +930,26 @@ __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const 
     using frag = typename E::frag;
     using TL = Tile<T, D>;
     constexpr int KVT = 128;                  // 4 pairs x 32 key rows
-    constexpr int QTL = 64;                   // query rows per LDS tile = 2 blocks
     constexpr int DC = D / 16;
     constexpr int DB = D / 32;
-    constexpr int NT = 512;
-    constexpr int NS = 3;                     // LDS stages
-    constexpr int TILE_BYTES = QTL * D * E::kBytes;
-    constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+    constexpr int NS = kDkvStages;            // LDS stages, one query block each
+    constexpr int AHEAD = NS - 2;             // a block is requested this many steps before the score waves' step
+    constexpr int BLK_BYTES = 32 * D * E::kBytes;
+    constexpr int STAGE_BYTES = 2 * BLK_BYTES;            // Q block, dO block
     constexpr int VEC_BASE = NS * STAGE_BYTES;
-    constexpr int VEC_STAGE = 3 * QTL * 4;
+    constexpr int VEC_STAGE = 3 * 32 * 4;                 // LSE*log2e, D, first token of the document
     constexpr int X_BASE = (VEC_BASE + NS * VEC_STAGE + 1023) & ~1023;
     constexpr int X_SLOT = 4 * 1024;          // P^T (2 chunks) and dS^T (2 chunks), 1 KiB per fragment
-    constexpr int NE = 4 * DB;
-    // LDS latency under load is several hundred cycles here, far more than a few matrix
-    // instructions: every fragment of a block is requested before its first matrix instruction
-    constexpr int PDR = DC;
-    constexpr int PDT = NE;
+    constexpr int NE = 4 * DB;                // matrix instructions of an update wave per block
+    constexpr int PDT = NE < 10 ? NE : 10;    // transposed fragments requested ahead of their use
     typedef __attribute__((address_space(3))) char lds_char;
+    typedef __attribute__((address_space(3))) frag lds_frag;
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
     const Geometry& geo = a.geo;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int role = wave >> 2;               // 0: score wave, 1: update wave
     const int pair = wave & 3;
     const int n = lane & 31, hh = lane >> 5;
@@ -958,153 +960,49 @@ __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const 
     const int wk_hi = min(wk0 + 31, Tn - 1);
     const int q_end = __builtin_amdgcn_readfirstlane(a.tok_end[min(kv_tile0 + KVT - 1, Tn - 1)]);
     const int wq_end = active ? __builtin_amdgcn_readfirstlane(a.tok_end[wk_hi]) : 0;
-    const bool wave_split = active && __builtin_amdgcn_readfirstlane(a.tok_start[wk_hi]) > wk0;
-    const int qt_lo = kv_tile0 / QTL;
-    const int qt_hi = (q_end - 1) / QTL;
-    const int nqt = qt_hi - qt_lo + 1;
+    const int qb_lo = kv_tile0 / 32;
+    const int nqb = (q_end - 1) / 32 - qb_lo + 1;     // query blocks that see a key of this tile
     const int n_jh = geo.n_steps * geo.G;
     const int n_c = (n_jh - sp + a.n_split - 1) / a.n_split;
-    const int n_it = n_c * nqt;               // query tiles this workgroup streams
-    const int n_blk = 2 * n_it;
+    const int n_blk = n_c * nqb;              // blocks this workgroup streams
     const float c = geo.scale_log2;
-    const int kvi = wk0 + n;
-
-    // per-lane LDS addresses inside stage 0
-    uint32_t ra[DC], ta[DB][2];
-    {
-        LaneFrags<T, D> lf;
-        lf.init(lane);
-#pragma unroll
-        for (int t = 0; t < DC; ++t) ra[t] = lds0 + lf.row[t];
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-            ta[db][0] = lds0 + lf.tr[db][0];
-            ta[db][1] = lds0 + lf.tr[db][1];
-        }
-    }
     const uint32_t xa = lds0 + X_BASE + pair * (2 * X_SLOT) + lane * 16;   // this lane's place in slot 0
-    const uint32_t va0 = lds0 + VEC_BASE + hh * 16;
 
-    auto ld_row = [&](uint32_t sb, int which, int qb, int t) -> frag {
-        return *reinterpret_cast<const __attribute__((address_space(3))) frag*>(
-            (uintptr_t)(ra[t] + sb + which * TILE_BYTES + qb * 32 * TL::kRowBytes));
-    };
-    auto ld_tr = [&](uint32_t sb, int which, int qb, int c2, int db) -> frag {
-        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-        const uint32_t off = sb + which * TILE_BYTES + (qb * 32 + c2 * 16) * TL::kRowBytes;
-        union { s16x4 s[2]; frag v; } u;
-        u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][0] + off));
-        u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][1] + off));
-        return u.v;
-    };
-    auto ld_vec = [&](uint32_t vb, int which, int qb, int i4) -> f32x4 {
-        return *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(
-            (uintptr_t)(va0 + vb + which * QTL * 4 + (qb * 32 + i4 * 8) * 4));
-    };
-
-    // Copy source of this thread inside a query tile, computed once: NLD pieces of the Q tile and of
-    // the dO tile per thread (same positions in both).  Only a tile that reaches past the last token
-    // needs its rows clamped.
-    constexpr int NLD = QTL * TL::kPieces / NT;
-    static_assert(2 * NLD + 3 <= 15, "partial vmcnt wait must fit the 4 low counter bits");
-    int64_t src_off[NLD];   // element offset of the piece inside the tile (token stride applied)
-    int src_row[NLD];
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-        const int pidx = (i * (NT / 64) + wave) * 64 + lane;
-        const int r = pidx / TL::kPieces, pos = pidx % TL::kPieces;
-        src_row[i] = r;
-        src_off[i] = (int64_t)r * geo.q_st + ((pos ^ TL::swz(r)) * TL::kElemsPerPiece);
-    }
-    // tile counter -> (step/head pair, query tile, LDS stage), advanced without divisions
-    int is_ci = 0, is_qt = qt_lo, is_stage = 0;
-    auto issue_next = [&]() {
-        const int jh = sp + is_ci * a.n_split;
-        const int js = jh / geo.G, h = g * geo.G + jh % geo.G;
-        const int j = geo.step_begin + js;
-        const T* Qj = static_cast<const T*>(a.q[j]) + (int64_t)h * geo.q_sh;
-        const T* dOj = static_cast<const T*>(a.d_o[j]) + (int64_t)h * geo.q_sh;
-        char* st = smem + is_stage * STAGE_BYTES;
-        const int row0 = is_qt * QTL;
-        typedef __attribute__((address_space(3))) void lds_void;
-        typedef const __attribute__((address_space(1))) void glb_void;
-        if (row0 + QTL <= Tn) {
-            const T* qb = Qj + (int64_t)row0 * geo.q_st;
-            const T* gb = dOj + (int64_t)row0 * geo.q_st;
-#pragma unroll
-            for (int i = 0; i < NLD; ++i) {
-                const int base = (i * (NT / 64) + wave) * 64 * 16;
-                __builtin_amdgcn_global_load_lds((glb_void*)(qb + src_off[i]), (lds_void*)(uintptr_t)(st + base), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((glb_void*)(gb + src_off[i]), (lds_void*)(uintptr_t)(st + TILE_BYTES + base), 16, 0, 0);
-            }
-        } else {
-            tile_load_async<T, D, QTL, NT>(st, Qj, geo.q_st, row0, Tn - 1, tid);
-            tile_load_async<T, D, QTL, NT>(st + TILE_BYTES, dOj, geo.q_st, row0, Tn - 1, tid);
-        }
-        if (tid < QTL) {
-            const int qq = min(row0 + tid, Tn - 1);
-            const int64_t at = ((int64_t)js * geo.hq + h) * Tn + qq;
-            char* vec = smem + VEC_BASE + is_stage * VEC_STAGE;
-            __builtin_amdgcn_global_load_lds((glb_void*)(a.lse2 + at), (lds_void*)(uintptr_t)vec, 4, 0, 0);
-            __builtin_amdgcn_global_load_lds((glb_void*)(a.delta + at), (lds_void*)(uintptr_t)(vec + QTL * 4), 4, 0, 0);
-            __builtin_amdgcn_global_load_lds((glb_void*)(a.tok_start + qq), (lds_void*)(uintptr_t)(vec + 2 * QTL * 4), 4, 0, 0);
-        }
-        if (++is_stage == NS) is_stage = 0;
-        if (++is_qt == qt_lo + nqt) {
-            is_qt = qt_lo;
-            ++is_ci;
-        }
-    };
-
-    // Walks the block sequence without divisions: block b lives in tile b/2, LDS stage (b/2) % NS,
-    // query tile qt_lo + (b/2) % nqt.
+    // Walks the block sequence without divisions: block b lives in LDS stage b % NS and is query
+    // block qb_lo + b % nqb of (step, head) pair number b / nqb of this workgroup's list.
     struct Cursor {
-        int stage, qt, qb;   // LDS stage, query tile index, block inside the tile
-        __device__ void next(int nqt_, int qt_lo_) {
-            if (++qb == 2) {
-                qb = 0;
-                if (++stage == NS) stage = 0;
-                if (++qt == qt_lo_ + nqt_) qt = qt_lo_;
+        int stage, qb, ci;
+        __device__ void next(int nqb_, int qb_lo_) {
+            if (++stage == NS) stage = 0;
+            if (++qb == qb_lo_ + nqb_) {
+                qb = qb_lo_;
+                ++ci;
             }
         }
     };
     auto visible = [&](const Cursor& cur) {
-        const int q0 = cur.qt * QTL + cur.qb * 32;
+        const int q0 = cur.qb * 32;
         return active && q0 + 31 >= wk0 && q0 < wq_end;
     };
-    // common to both roles at the top of step s: tile s/2 + 2 goes into the stage that the update
-    // waves left at the end of step s - 1
-    // Copies, common to both roles.  At the top of an odd step s, tile s/2 + 2 is requested into the
-    // stage that the update waves left at the end of step s - 1; at the bottom of that step, before
-    // its barrier, the wave waits until only those newest requests are outstanding, i.e. until
-    // tile s/2 + 1 (needed from step s + 1 on, requested two steps ago) has landed.
-    auto step_copies_top = [&](int s) -> bool {
-        if ((s & 1) && (s >> 1) + 2 < n_it) {
-            issue_next();
-            return true;
-        }
-        return false;
-    };
-    auto step_copies_bottom = [&](int s, bool issued) {
-        if (!(s & 1) || (s >> 1) + 1 >= n_it) return;
-        if (!issued) {
-            wait_async_copies();
-        } else if (wave == 0) {
-            __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * NLD + 3));   // vmcnt = this wave's newest requests
-        } else {
-            __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * NLD));
-        }
-    };
 
-    if (n_it > 0) issue_next();
-    if (n_it > 1) issue_next();
-    wait_async_copies();
-    __syncthreads();
-
-    // The two roles run separate loops with the same number of barriers (n_blk + 1), so that each
-    // role's registers hold only its own state.
     if (role == 0) {
-        // ---- score waves: K_0, V_0 rows of the pair as stationary B operands
+        // ================================ score waves ================================
+        uint32_t ra[DC];
+        {
+            LaneFrags<T, D> lf;
+            lf.init(lane);
+#pragma unroll
+            for (int t = 0; t < DC; ++t) ra[t] = lds0 + lf.row[t];
+        }
+        const uint32_t va0 = lds0 + VEC_BASE + hh * 16;
+        auto ld_row = [&](uint32_t sb, int which, int t) -> frag {
+            return *reinterpret_cast<const lds_frag*>((uintptr_t)(ra[t] + sb + which * BLK_BYTES));
+        };
+        auto ld_vec = [&](uint32_t vb, int which, int i4) -> f32x4 {
+            return *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(
+                (uintptr_t)(va0 + vb + which * 128 + i4 * 32));
+        };
+        // K_0, V_0 rows of the pair as stationary B operands
         frag kf[DC], vf[DC];
         {
             const T* K0 = static_cast<const T*>(a.k[0]) + (int64_t)g * geo.kv_sh;
@@ -1116,41 +1014,54 @@ __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const 
                 vf[t] = gload_frag<T>(V0 + (int64_t)kc * geo.kv_st + t * 16 + hh * 8);
             }
         }
+        const bool wave_split = active && __builtin_amdgcn_readfirstlane(a.tok_start[wk_hi]) > wk0;
+        const int kvi = wk0 + n;
+        __syncthreads();                 // blocks 0 .. AHEAD-1 have landed
         __builtin_amdgcn_s_setprio(2);   // the score waves' matrix instructions go first: their vector
                                          // work then runs while the update waves use the matrix core
-        Cursor cur{0, qt_lo, 0};
-        for (int s = 0; s <= n_blk; ++s, cur.next(nqt, qt_lo)) {
-            const bool issued = step_copies_top(s);
-            if (s < n_blk && visible(cur)) {
-                const int b = s, qb = cur.qb;
-                const uint32_t sb = cur.stage * STAGE_BYTES;
-                const uint32_t vb = cur.stage * VEC_STAGE;
-                const int q0 = cur.qt * QTL + qb * 32;
-                frag qa[DC], ga[DC];
-                f32x16 sacc, pacc;
+        Cursor cur{0, qb_lo, 0};
+        frag qa[DC], ga[DC];             // row fragments of the block about to be scored
+        if (n_blk > 0 && visible(cur)) {
 #pragma unroll
-                for (int t = 0; t < PDR; ++t) {
-                    qa[t] = ld_row(sb, 0, qb, t);
-                    ga[t] = ld_row(sb, 1, qb, t);
-                }
-                f32x4 l4[4], d4[4];
+            for (int t = 0; t < DC; ++t) {
+                qa[t] = ld_row(0, 0, t);
+                ga[t] = ld_row(0, 1, t);
+            }
+        }
+        for (int s = 0; s <= n_blk; ++s) {
+            Cursor nxt = cur;
+            nxt.next(nqb, qb_lo);
+            const bool fetch_next = s + 1 < n_blk && visible(nxt);
+            const uint32_t nsb = nxt.stage * STAGE_BYTES;
+            const bool vis = s < n_blk && visible(cur);
+            const uint32_t vb = cur.stage * VEC_STAGE;
+            const int q0 = cur.qb * 32;
+            f32x16 sacc, pacc;
+            f32x4 l4[4], d4[4];
+            if (vis) {
 #pragma unroll
                 for (int i4 = 0; i4 < 4; ++i4) {
-                    l4[i4] = ld_vec(vb, 0, qb, i4);
-                    d4[i4] = ld_vec(vb, 1, qb, i4);
+                    l4[i4] = ld_vec(vb, 0, i4);
+                    d4[i4] = ld_vec(vb, 1, i4);
                 }
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sacc[i] = pacc[i] = 0.f;
 #pragma unroll
                 for (int t = 0; t < DC; ++t) {
-                    if (t + PDR < DC) {
-                        qa[t + PDR] = ld_row(sb, 0, qb, t + PDR);
-                        ga[t + PDR] = ld_row(sb, 1, qb, t + PDR);
-                    }
-                    issue_fence();
                     sacc = mma(qa[t], kf[t], sacc);
                     pacc = mma(ga[t], vf[t], pacc);
                 }
+            }
+            issue_fence();
+            if (fetch_next) {
+#pragma unroll
+                for (int t = 0; t < DC; ++t) {
+                    qa[t] = ld_row(nsb, 0, t);
+                    ga[t] = ld_row(nsb, 1, t);
+                }
+            }
+            issue_fence();
+            if (vis) {
                 // every row of the block sees every key of the pair iff the block lies at or below
                 // the pair's last key, ends before that key's document does, and the pair's keys are
                 // all in one document
@@ -1158,7 +1069,7 @@ __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const 
                 if (need_mask) {
 #pragma unroll
                     for (int x = 0; x < 16; ++x) {
-                        const f32x4 s4 = ld_vec(vb, 2, qb, x / 4);
+                        const f32x4 s4 = ld_vec(vb, 2, x / 4);
                         const int q = q0 + acc_row(x, hh);
                         float p = fast_exp2(fmaf(sacc[x], c, -l4[x / 4][x % 4]));
                         p = (kvi <= q && q < wq_end && kvi >= __float_as_int(s4[x % 4])) ? p : 0.f;
@@ -1174,54 +1085,162 @@ __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const 
                     }
                 }
                 // hand P^T and dS^T over as operand fragments
-                const uint32_t xs = xa + (b & 1) * X_SLOT;
+                const uint32_t xs = xa + (s & 1) * X_SLOT;
 #pragma unroll
                 for (int c2 = 0; c2 < 2; ++c2) {
-                    *reinterpret_cast<__attribute__((address_space(3))) frag*>((uintptr_t)(xs + c2 * 1024)) = acc_chunk<T>(sacc, c2);
-                    *reinterpret_cast<__attribute__((address_space(3))) frag*>((uintptr_t)(xs + (2 + c2) * 1024)) = acc_chunk<T>(pacc, c2);
+                    *reinterpret_cast<lds_frag*>((uintptr_t)(xs + c2 * 1024)) = acc_chunk<T>(sacc, c2);
+                    *reinterpret_cast<lds_frag*>((uintptr_t)(xs + (2 + c2) * 1024)) = acc_chunk<T>(pacc, c2);
                 }
             }
-            step_copies_bottom(s, issued);
-            __syncthreads();   // fragments of block s are visible; slot and stage of block s-1 are free
+            cur = nxt;
+            lds_barrier();   // fragments of block s are visible; slot and stage of block s-1 are free
         }
         return;
     }
 
-    // ---- update waves: one block behind
+    // ================================ update waves: one block behind ================================
+    uint32_t ta[DB][2];
+    {
+        LaneFrags<T, D> lf;
+        lf.init(lane);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            ta[db][0] = lds0 + lf.tr[db][0];
+            ta[db][1] = lds0 + lf.tr[db][1];
+        }
+    }
+    auto ld_tr = [&](uint32_t sb, int which, int c2, int db) -> frag {
+        const uint32_t off = sb + which * BLK_BYTES + c2 * 16 * TL::kRowBytes;
+        union { s16x4 s[2]; frag v; } u;
+        u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][0] + off));
+        u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][1] + off));
+        return u.v;
+    };
+
+    // ---- copies: 32 x kPieces 16-byte pieces per matrix and block over the 256 update threads
+    constexpr int NLD = 32 * TL::kPieces / 256;
+    constexpr int PER = 2 * NLD;              // requests per block of waves 5..7; wave 4 adds 3
+    static_assert((AHEAD - 2) * (PER + 3) <= 21, "partial waits are written out up to 21 requests");
+    const int uw = wave - 4, ut = tid - 256;
+    // Per thread, once: where its pieces sit inside a block (byte offset from the block's first row;
+    // the host checks that 32 rows fit 32 bits).  Per block, only scalar work is left: a 64-bit
+    // base per matrix and the LDS destination.
+    int src_r[NLD], src_c[NLD];
+    uint32_t src_off[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int pidx = (i * 4 + uw) * 64 + lane;
+        const int r = pidx / TL::kPieces, pos = pidx % TL::kPieces;
+        src_r[i] = r;
+        src_c[i] = (pos ^ TL::swz(r)) * TL::kElemsPerPiece;
+        src_off[i] = (uint32_t)((r * geo.q_st + src_c[i]) * (int64_t)sizeof(T));
+    }
+    const uint32_t vec_off = (uint32_t)(lane & 31) * 4;
+    Cursor iss{0, qb_lo, 0};                  // next block to request
+    int iss_ci = -1;
+    const T *iss_q = nullptr, *iss_g = nullptr;
+    int64_t iss_at = 0;
+    auto issue_next = [&]() {
+        if (iss.ci != iss_ci) {
+            iss_ci = iss.ci;
+            const int jh = sp + iss_ci * a.n_split;
+            const int js = jh / geo.G, h = g * geo.G + jh % geo.G;
+            const int j = geo.step_begin + js;
+            iss_q = static_cast<const T*>(a.q[j]) + (int64_t)h * geo.q_sh;
+            iss_g = static_cast<const T*>(a.d_o[j]) + (int64_t)h * geo.q_sh;
+            iss_at = ((int64_t)js * geo.hq + h) * Tn;
+        }
+        const uint32_t st = lds0 + iss.stage * STAGE_BYTES;
+        const uint32_t vec = lds0 + VEC_BASE + iss.stage * VEC_STAGE;
+        const int row0 = iss.qb * 32;
+        if (row0 + 32 <= Tn) {
+            const T* bq = iss_q + (int64_t)row0 * geo.q_st;
+            const T* bg = iss_g + (int64_t)row0 * geo.q_st;
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                const int base = (i * 4 + uw) * 1024;
+                async_copy16(bq, src_off[i], st + base);
+                async_copy16(bg, src_off[i], st + BLK_BYTES + base);
+            }
+            if (ut < 32) {
+                async_copy4(a.lse2 + iss_at + row0, vec_off, vec);
+                async_copy4(a.delta + iss_at + row0, vec_off, vec + 128);
+                async_copy4(a.tok_start + row0, vec_off, vec + 256);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                const int row = min(row0 + src_r[i], Tn - 1);     // rows past the end are masked later
+                const int64_t off = (int64_t)row * geo.q_st + src_c[i];
+                const int base = (i * 4 + uw) * 1024;
+                async_copy16(iss_q + off, st + base);
+                async_copy16(iss_g + off, st + BLK_BYTES + base);
+            }
+            if (ut < 32) {
+                const int qq = min(row0 + ut, Tn - 1);
+                async_copy4(a.lse2 + iss_at + qq, vec);
+                async_copy4(a.delta + iss_at + qq, vec + 128);
+                async_copy4(a.tok_start + qq, vec + 256);
+            }
+        }
+        iss.next(nqb, qb_lo);
+    };
+#pragma unroll 1
+    for (int b = 0; b < AHEAD && b < n_blk; ++b) issue_next();
+
     f32x16 dkacc[DB], dvacc[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) dkacc[db][i] = dvacc[db][i] = 0.f;
-    Cursor cur{0, qt_lo, 0};   // block s - 1
+
+    wait_async_copies();
+    __syncthreads();
+
+    // The transposed dO / Q fragments of a block do not depend on the score waves: the first PDT of
+    // them are requested one step early, before the barrier that publishes the block's P and dS.
+    // transposed fragment x = (c2 * DB + db) * 2 + (0: dO for dV, 1: Q for dK)
+    auto ld_tfr = [&](uint32_t sb, int x) -> frag { return ld_tr(sb, 1 - (x & 1), (x >> 1) / DB, (x >> 1) % DB); };
+    Cursor cur{0, qb_lo, 0};   // block s - 1 (after the advance below: block s)
+    frag tfr[NE];
     for (int s = 0; s <= n_blk; ++s) {
-        const bool issued = step_copies_top(s);
-        if (s >= 1 && visible(cur)) {
-            const int b = s - 1, qb = cur.qb;
-            const uint32_t sb = cur.stage * STAGE_BYTES;
-            const uint32_t xs = xa + (b & 1) * X_SLOT;
-            frag pfr[2], sfr[2], tfr[NE];
+        // block s + AHEAD goes into the stage that block s - 2 left at the end of step s - 1
+        if (s + AHEAD < n_blk) issue_next();
+        if (s >= 1) {
+            if (visible(cur)) {
+                const uint32_t sb = cur.stage * STAGE_BYTES;
+                const uint32_t xs = xa + ((s - 1) & 1) * X_SLOT;
+                frag pfr[2], sfr[2];
 #pragma unroll
-            for (int c2 = 0; c2 < 2; ++c2) {
-                pfr[c2] = *reinterpret_cast<const __attribute__((address_space(3))) frag*>((uintptr_t)(xs + c2 * 1024));
-                sfr[c2] = *reinterpret_cast<const __attribute__((address_space(3))) frag*>((uintptr_t)(xs + (2 + c2) * 1024));
+                for (int c2 = 0; c2 < 2; ++c2) {
+                    pfr[c2] = *reinterpret_cast<const lds_frag*>((uintptr_t)(xs + c2 * 1024));
+                    sfr[c2] = *reinterpret_cast<const lds_frag*>((uintptr_t)(xs + (2 + c2) * 1024));
+                }
+#pragma unroll
+                for (int x = 0; x < NE; ++x) {
+                    if (x + PDT < NE) tfr[x + PDT] = ld_tfr(sb, x + PDT);
+                    issue_fence();
+                    const int c2 = (x >> 1) / DB, db = (x >> 1) % DB;
+                    if (x & 1) dkacc[db] = mma(sfr[c2], tfr[x], dkacc[db]);
+                    else       dvacc[db] = mma(pfr[c2], tfr[x], dvacc[db]);
+                }
             }
-            // transposed fragment x = (c2 * DB + db) * 2 + (0: dO for dV, 1: Q for dK)
-            auto ld_tfr = [&](int x) -> frag { return ld_tr(sb, 1 - (x & 1), qb, (x >> 1) / DB, (x >> 1) % DB); };
-#pragma unroll
-            for (int x = 0; x < PDT; ++x) tfr[x] = ld_tfr(x);
-#pragma unroll
-            for (int x = 0; x < NE; ++x) {
-                if (x + PDT < NE) tfr[x + PDT] = ld_tfr(x + PDT);
-                issue_fence();
-                const int c2 = (x >> 1) / DB, db = (x >> 1) % DB;
-                if (x & 1) dkacc[db] = mma(sfr[c2], tfr[x], dkacc[db]);
-                else       dvacc[db] = mma(pfr[c2], tfr[x], dvacc[db]);
-            }
+            cur.next(nqb, qb_lo);
         }
-        if (s >= 1) cur.next(nqt, qt_lo);
-        step_copies_bottom(s, issued);
-        __syncthreads();
+        issue_fence();
+        if (s < n_blk && visible(cur)) {
+            const uint32_t sb = cur.stage * STAGE_BYTES;
+#pragma unroll
+            for (int x = 0; x < PDT; ++x) tfr[x] = ld_tfr(sb, x);
+        }
+        // The score waves fetch block s + 2 right after this barrier (during step s + 1): it must
+        // have landed; the requests for the (up to two) blocks after it may stay in flight.
+        if (s + 2 < n_blk) {
+            const int newer = min(s + AHEAD, n_blk - 1) - (s + 2);
+            const int per = uw == 0 ? PER + 3 : PER;
+            wait_copies_but(newer * per);
+        }
+        bare_barrier();   // the fragments requested above are not waited for here
     }
     if (!active) return;
 #pragma unroll
@@ -1378,7 +1397,7 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
     {
         constexpr bool kWs = sizeof(T) == 2;      // wave-specialised kernel for 16-bit types
         constexpr int KVT = kWs ? 128 : NW_KV * 32;
-        constexpr int WS_LDS = ((3 * 2 * 64 * D * 2 + 3 * 3 * 64 * 4 + 1023) & ~1023) + 4 * 2 * 4096;
+        constexpr int WS_LDS = ((kDkvStages * 2 * 32 * D * 2 + kDkvStages * 3 * 32 * 4 + 1023) & ~1023) + 4 * 2 * 4096;
         constexpr int LDS = kWs ? WS_LDS : 2 * (2 * 64 * D * (int)sizeof(T) + 3 * 64 * 4);
         const void* kern;
         if constexpr (kWs) kern = (const void*)ttt_bwd_dkv_ws_kernel<T, D>;
@@ -1389,6 +1408,8 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
             if (e != hipSuccess) return e;
             attr_done = true;
         }
+        // the wave-specialised kernel addresses the rows of a 32-row block with 32-bit byte offsets
+        if (kWs && geo.q_st * 32 * (int64_t)sizeof(T) >= (int64_t)1 << 32) return hipErrorInvalidValue;
         a.n_tiles = (geo.T + KVT - 1) / KVT;
         // split the (step, head) list of a kv tile so that the grid has a few thousand workgroups
         const int n_jh = geo.n_steps * geo.G;

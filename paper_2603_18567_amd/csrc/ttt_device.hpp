@@ -212,6 +212,36 @@ TTT_DEV void issue_fence() {
 // compile-time integer handed to generic lambdas (pipeline stage)
 template <int V> struct IntC { static constexpr int value = V; };
 
+// ---- global -> LDS copy requests (LDS-DMA loads), 16 or 4 bytes per lane: the wave's 64 pieces land
+// at lds_dst + lane * size, lds_dst being wave-uniform (it travels in M0).  Written as inline
+// assembly on purpose: for the builtin form the compiler cannot tell which LDS reads depend on a
+// pending copy and makes every transposing LDS read wait for ALL outstanding copies of the wave,
+// which serialises a copy with the work it was meant to overlap.  Here the program states the
+// dependency itself: wait_async_copies() (or a partial vmcnt wait) plus a barrier before the first
+// read of a stage.  The compiler keeps no value in M0 across statements (reserved register).
+TTT_DEV uint32_t lds_addr(const void* p) {
+    typedef __attribute__((address_space(3))) char lds_char;
+    return (uint32_t)(uintptr_t)(lds_char*)p;
+}
+TTT_DEV void async_copy16(const void* gsrc, uint32_t lds_dst) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_dst)), "v"(gsrc) : "memory");
+}
+TTT_DEV void async_copy4(const void* gsrc, uint32_t lds_dst) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_dst)), "v"(gsrc) : "memory");
+}
+
+// the same with the source given as a wave-uniform 64-bit base plus a 32-bit byte offset per lane
+TTT_DEV void async_copy16(const void* gbase, uint32_t lane_off, uint32_t lds_dst) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_dst)), "v"(lane_off), "s"(gbase) : "memory");
+}
+TTT_DEV void async_copy4(const void* gbase, uint32_t lane_off, uint32_t lds_dst) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :: "s"(__builtin_amdgcn_readfirstlane(lds_dst)), "v"(lane_off), "s"(gbase) : "memory");
+}
+
 // ---- global -> LDS tile copy without passing through registers (16 bytes per lane per
 // instruction; one wave instruction fills 1024 contiguous LDS bytes).  ROWS*kRowBytes must be a
 // multiple of NTHREADS*16.  Rows are clamped to [0, max_row] so the copy never leaves the tensor;
@@ -233,14 +263,37 @@ TTT_DEV void tile_load_async(char* tile, const T* g, int64_t stride_token, int r
         int gr = row_first + r;
         gr = gr > max_row ? max_row : gr;
         const T* src = g + (int64_t)gr * stride_token + piece * TL::kElemsPerPiece;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                         (__attribute__((address_space(3))) void*)(uintptr_t)(tile + base * 16),
-                                         16, 0, 0);
+        async_copy16(src, lds_addr(tile + base * 16));
     }
 }
 
+// Workgroup barrier for data handed over through LDS only: this wave's LDS accesses are complete,
+// but its outstanding global-memory requests (copies into LDS stages that nobody reads yet) stay
+// in flight -- __syncthreads() would wait for them too.
+TTT_DEV void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// The bare barrier, for a wave whose LDS traffic before it consists of reads that have already been
+// consumed (so they are complete) plus reads of data that stays valid past the barrier.
+TTT_DEV void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
 // all outstanding global->LDS copies of this wave have landed
 TTT_DEV void wait_async_copies() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+
+// Waits until at most n (wave-uniform, 0..21) of this wave's global-memory requests are outstanding.
+// Requests complete in order, so the n newest may stay in flight.  The count sits in bits 3:0 and
+// 15:14 of the immediate; the other counters are left alone.
+TTT_DEV void wait_copies_but(int n) {
+#define TTT_VMCNT_CASE(N) case N: __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14)); break;
+    switch (n) {
+        TTT_VMCNT_CASE(1) TTT_VMCNT_CASE(2) TTT_VMCNT_CASE(3) TTT_VMCNT_CASE(4) TTT_VMCNT_CASE(5)
+        TTT_VMCNT_CASE(6) TTT_VMCNT_CASE(7) TTT_VMCNT_CASE(8) TTT_VMCNT_CASE(9) TTT_VMCNT_CASE(10)
+        TTT_VMCNT_CASE(11) TTT_VMCNT_CASE(12) TTT_VMCNT_CASE(13) TTT_VMCNT_CASE(14) TTT_VMCNT_CASE(15)
+        TTT_VMCNT_CASE(16) TTT_VMCNT_CASE(17) TTT_VMCNT_CASE(18) TTT_VMCNT_CASE(19) TTT_VMCNT_CASE(20)
+        TTT_VMCNT_CASE(21)
+        default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+    }
+#undef TTT_VMCNT_CASE
+}
 
 // ---- small helpers
 TTT_DEV float xor32(float v) { return __shfl_xor(v, 32, 64); }
