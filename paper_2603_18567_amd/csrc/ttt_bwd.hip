@@ -627,22 +627,66 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
                 }
             };
 
-            prime_rows(0);
+            if constexpr (NW == 8) {
+                // Two waves per SIMD: no pipelining inside the wave.  One wave's vector work runs
+                // while the other wave of the SIMD uses the matrix core (they fall into opposite
+                // phases by themselves); blocks that this wave's rows cannot see are skipped.
+                bool primed = false;
 #pragma unroll
-            for (int kb = 0; kb < NB; ++kb) {
-                score(kb);
-                if (kb + 1 < NB) prime_rows(kb + 1);
-                const int kb0 = kv0 + kb * 32;
-                const bool need_mask = kb0 + 31 > wq0 || kb0 < st_hi;
-                if (kb == 0) {
-                    if (need_mask) fused(IntC<1>{}, IntC<0>{}, IntC<1>{}, kb);
-                    else fused(IntC<1>{}, IntC<0>{}, IntC<0>{}, kb);
-                } else {
-                    if (need_mask) fused(IntC<1>{}, IntC<1>{}, IntC<1>{}, kb);
-                    else fused(IntC<1>{}, IntC<1>{}, IntC<0>{}, kb);
+                for (int kb = 0; kb < NB; ++kb) {
+                    const int kb0 = kv0 + kb * 32;
+                    if (kb0 > hi_w || kb0 + 31 < lo_w) {
+                        primed = false;
+                        continue;
+                    }
+                    if (!primed) prime_rows(kb);
+                    score(kb);
+                    // requests that do not depend on the vector work below
+#pragma unroll
+                    for (int x = 0; x < PDT; ++x) tfr[x] = ld_ktr(kb, x);
+                    primed = kb + 1 < NB && !(kb0 + 32 > hi_w || kb0 + 63 < lo_w);
+                    if (primed) prime_rows(kb + 1);
+                    issue_fence();
+                    const bool need_mask = kb0 + 31 > wq0 || kb0 < st_hi;
+                    if (need_mask) {
+#pragma unroll
+                        for (int x = 0; x < 16; ++x) {
+                            const int kv = kb0 + acc_row(x, hh);
+                            float p = fast_exp2(fmaf(sacc[x], c, -lse2));
+                            p = (kv <= qi && kv >= st) ? p : 0.f;
+                            pacc[x] = p * (pacc[x] - dl);   // dS^T
+                        }
+                    } else {
+#pragma unroll
+                        for (int x = 0; x < 16; ++x) pacc[x] = fast_exp2(fmaf(sacc[x], c, -lse2)) * (pacc[x] - dl);
+                    }
+                    sfr[0] = acc_chunk<T>(pacc, 0);
+                    sfr[1] = acc_chunk<T>(pacc, 1);
+#pragma unroll
+                    for (int x = 0; x < NE; ++x) {
+                        if (x + PDT < NE) tfr[x + PDT] = ld_ktr(kb, x + PDT);
+                        issue_fence();
+                        dqacc[x % DB] = mma(tfr[x], sfr[x / DB], dqacc[x % DB]);
+                    }
                 }
+            } else {
+                prime_rows(0);
+#pragma unroll
+                for (int kb = 0; kb < NB; ++kb) {
+                    score(kb);
+                    if (kb + 1 < NB) prime_rows(kb + 1);
+                    const int kb0 = kv0 + kb * 32;
+                    const bool need_mask = kb0 + 31 > wq0 || kb0 < st_hi;
+                    if (kb == 0) {
+                        if (need_mask) fused(IntC<1>{}, IntC<0>{}, IntC<1>{}, kb);
+                        else fused(IntC<1>{}, IntC<0>{}, IntC<0>{}, kb);
+                    } else {
+                        if (need_mask) fused(IntC<1>{}, IntC<1>{}, IntC<1>{}, kb);
+                        else fused(IntC<1>{}, IntC<1>{}, IntC<0>{}, kb);
+                    }
+                }
+                fused(IntC<0>{}, IntC<1>{}, IntC<0>{}, NB - 1);
             }
-            fused(IntC<0>{}, IntC<1>{}, IntC<0>{}, NB - 1);
         }
 #pragma unroll
         for (int t = 0; t < DC; ++t) ra[t] ^= STAGE_BYTES;
@@ -671,13 +715,13 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
         request(1);
         for (int lb = 1; lb <= j; ++lb) {
             float s = 0.f, dp = 0.f;
-            float kk[DB][16];   // the key row in accumulator order
+            uint32_t kk[DC][4];   // the key row in accumulator order, still packed
 #pragma unroll
             for (int t = 0; t < DC; ++t) {
                 s = dot8(qf[t], dk[t], s);
                 dp = dot8(gof[t], dv[t], dp);
             }
-            frags_to_acc_order<T, DC>(dk, kk);
+            frags_to_acc_order_packed<T, DC>(dk, kk);
             if (lb < j) request(lb + 1);
             s = half_sum(s);
             dp = half_sum(dp);
@@ -686,7 +730,7 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) dqacc[db][i] = fmaf(ds, kk[db][i], dqacc[db][i]);
+                for (int i = 0; i < 16; ++i) dqacc[db][i] = fmaf(ds, acc_order_elem<DC>(kk, db, i), dqacc[db][i]);
         }
     }
 
@@ -1136,10 +1180,14 @@ __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const 
         src_off[i] = (uint32_t)((r * geo.q_st + src_c[i]) * (int64_t)sizeof(T));
     }
     const uint32_t vec_off = (uint32_t)(lane & 31) * 4;
+    // Running state of the request stream: the (step, head) pair's base pointers change when the
+    // block sequence wraps around; from one block to the next only additions are left.
     Cursor iss{0, qb_lo, 0};                  // next block to request
     int iss_ci = -1;
-    const T *iss_q = nullptr, *iss_g = nullptr;
-    int64_t iss_at = 0;
+    const T *iss_q = nullptr, *iss_g = nullptr;           // row 0 of the pair's Q / dO
+    const float *iss_l = nullptr, *iss_d = nullptr;       // row 0 of the pair's LSE*log2e / D
+    const int64_t blk_step = 32 * geo.q_st;
+    const T *cur_q = nullptr, *cur_g = nullptr;           // first row of the next block
     auto issue_next = [&]() {
         if (iss.ci != iss_ci) {
             iss_ci = iss.ci;
@@ -1148,23 +1196,25 @@ __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const 
             const int j = geo.step_begin + js;
             iss_q = static_cast<const T*>(a.q[j]) + (int64_t)h * geo.q_sh;
             iss_g = static_cast<const T*>(a.d_o[j]) + (int64_t)h * geo.q_sh;
-            iss_at = ((int64_t)js * geo.hq + h) * Tn;
+            const int64_t at = ((int64_t)js * geo.hq + h) * Tn;
+            iss_l = a.lse2 + at;
+            iss_d = a.delta + at;
+            cur_q = iss_q + (int64_t)qb_lo * blk_step;
+            cur_g = iss_g + (int64_t)qb_lo * blk_step;
         }
         const uint32_t st = lds0 + iss.stage * STAGE_BYTES;
         const uint32_t vec = lds0 + VEC_BASE + iss.stage * VEC_STAGE;
         const int row0 = iss.qb * 32;
         if (row0 + 32 <= Tn) {
-            const T* bq = iss_q + (int64_t)row0 * geo.q_st;
-            const T* bg = iss_g + (int64_t)row0 * geo.q_st;
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
                 const int base = (i * 4 + uw) * 1024;
-                async_copy16(bq, src_off[i], st + base);
-                async_copy16(bg, src_off[i], st + BLK_BYTES + base);
+                async_copy16(cur_q, src_off[i], st + base);
+                async_copy16(cur_g, src_off[i], st + BLK_BYTES + base);
             }
             if (ut < 32) {
-                async_copy4(a.lse2 + iss_at + row0, vec_off, vec);
-                async_copy4(a.delta + iss_at + row0, vec_off, vec + 128);
+                async_copy4(iss_l + row0, vec_off, vec);
+                async_copy4(iss_d + row0, vec_off, vec + 128);
                 async_copy4(a.tok_start + row0, vec_off, vec + 256);
             }
         } else {
@@ -1178,11 +1228,13 @@ __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const 
             }
             if (ut < 32) {
                 const int qq = min(row0 + ut, Tn - 1);
-                async_copy4(a.lse2 + iss_at + qq, vec);
-                async_copy4(a.delta + iss_at + qq, vec + 128);
+                async_copy4(iss_l + qq, vec);
+                async_copy4(iss_d + qq, vec + 128);
                 async_copy4(a.tok_start + qq, vec + 256);
             }
         }
+        cur_q += blk_step;
+        cur_g += blk_step;
         iss.next(nqb, qb_lo);
     };
 #pragma unroll 1
@@ -1236,9 +1288,20 @@ __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const 
         // The score waves fetch block s + 2 right after this barrier (during step s + 1): it must
         // have landed; the requests for the (up to two) blocks after it may stay in flight.
         if (s + 2 < n_blk) {
+            // (a few explicit cases: the immediate of the wait instruction is a compile-time constant)
+            static_assert(AHEAD <= 5, "cases below");
             const int newer = min(s + AHEAD, n_blk - 1) - (s + 2);
-            const int per = uw == 0 ? PER + 3 : PER;
-            wait_copies_but(newer * per);
+            if (uw == 0) {
+                if (newer == AHEAD - 2) wait_copies_but(IntC<(AHEAD - 2) * (PER + 3)>{});
+                else if (newer == 2) wait_copies_but(IntC<2 * (PER + 3)>{});
+                else if (newer == 1) wait_copies_but(IntC<PER + 3>{});
+                else wait_async_copies();
+            } else {
+                if (newer == AHEAD - 2) wait_copies_but(IntC<(AHEAD - 2) * PER>{});
+                else if (newer == 2) wait_copies_but(IntC<2 * PER>{});
+                else if (newer == 1) wait_copies_but(IntC<PER>{});
+                else wait_async_copies();
+            }
         }
         bare_barrier();   // the fragments requested above are not waited for here
     }

@@ -279,20 +279,12 @@ TTT_DEV void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
 // all outstanding global->LDS copies of this wave have landed
 TTT_DEV void wait_async_copies() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
-// Waits until at most n (wave-uniform, 0..21) of this wave's global-memory requests are outstanding.
-// Requests complete in order, so the n newest may stay in flight.  The count sits in bits 3:0 and
-// 15:14 of the immediate; the other counters are left alone.
-TTT_DEV void wait_copies_but(int n) {
-#define TTT_VMCNT_CASE(N) case N: __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14)); break;
-    switch (n) {
-        TTT_VMCNT_CASE(1) TTT_VMCNT_CASE(2) TTT_VMCNT_CASE(3) TTT_VMCNT_CASE(4) TTT_VMCNT_CASE(5)
-        TTT_VMCNT_CASE(6) TTT_VMCNT_CASE(7) TTT_VMCNT_CASE(8) TTT_VMCNT_CASE(9) TTT_VMCNT_CASE(10)
-        TTT_VMCNT_CASE(11) TTT_VMCNT_CASE(12) TTT_VMCNT_CASE(13) TTT_VMCNT_CASE(14) TTT_VMCNT_CASE(15)
-        TTT_VMCNT_CASE(16) TTT_VMCNT_CASE(17) TTT_VMCNT_CASE(18) TTT_VMCNT_CASE(19) TTT_VMCNT_CASE(20)
-        TTT_VMCNT_CASE(21)
-        default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
-    }
-#undef TTT_VMCNT_CASE
+// Waits until at most N of this wave's global-memory requests are outstanding.  Requests complete
+// in order, so the N newest may stay in flight.  The count sits in bits 3:0 and 15:14 of the
+// immediate; the other counters are left alone.
+template <int N> TTT_DEV void wait_copies_but(IntC<N>) {
+    static_assert(N >= 0 && N < 64, "6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
 // ---- small helpers
@@ -354,6 +346,30 @@ template <typename T, int DC> TTT_DEV void frags_to_acc_order(const typename Ele
             out[db][(i4 + 1) * 4 + x] = to_f32<T>(odd.e[x]);
         }
     }
+}
+
+// The same reordering for 16-bit elements, left packed (two elements per register) so that the row
+// costs half the registers until its values are used: out[t] = {even pair 0, even pair 1, odd pair 0,
+// odd pair 1} of fragment t; acc_order_elem() unpacks accumulator element i of 32-column block db.
+template <typename T, int DC> TTT_DEV void frags_to_acc_order_packed(const typename Elem<T>::frag (&f)[DC], uint32_t (&out)[DC][4]) {
+    static_assert(sizeof(T) == 2, "packed form is for 16-bit elements");
+    union U { typename Elem<T>::frag v; uint32_t r[4]; };
+#pragma unroll
+    for (int t = 0; t < DC; ++t) {
+        U u;
+        u.v = f[t];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const auto sw = __builtin_amdgcn_permlane32_swap(u.r[i], u.r[i + 2], false, false);
+            out[t][i] = sw[0];
+            out[t][2 + i] = sw[1];
+        }
+    }
+}
+template <int DC> TTT_DEV float acc_order_elem(const uint32_t (&p)[DC][4], int db, int i) {
+    const int i4 = i / 4, x = i % 4;
+    const uint32_t r = p[2 * db + i4 / 2][2 * (i4 % 2) + x / 2];
+    return __uint_as_float((x % 2) ? (r & 0xffff0000u) : (r << 16));   // bf16 -> fp32 is a shift
 }
 
 // load 8 consecutive elements from global as a fragment
