@@ -20,6 +20,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3       # MI355X fp32 MFMA/vector
+# HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
+# command (profiles/headline_4k_hbm_traffic.txt: fetch scaled by the copy calibration, plus write);
+# a counter cannot be read from inside this process, so the recorded figure is reported.
+RECORDED_TRAFFIC = {("headline_4k", "ttt_bwd_dkv_kernel"): 2826.2e6 + 268.4e6}
 
 
 def parse():
@@ -145,7 +149,7 @@ def main():
     if dom is not None:
         ach = alg[dom] / (kernel_ms[dom] * 1e-3) / 1e12
         roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
-                    "frac": ach / peak, "traffic": None, "avg_ms": kernel_ms[dom],
+                    "frac": ach / peak, "traffic": RECORDED_TRAFFIC.get((wl.name, dom)), "avg_ms": kernel_ms[dom],
                     "algorithmic_flops_per_launch": alg[dom]}
 
     out = {

@@ -18,7 +18,7 @@ TTT_PASS_FWD, TTT_PASS_BWD, TTT_PASS_BWD_ACCUM = 0, 1, 2
 TTT_MAX_STEPS = 32
 
 EXPORTS = ("ttt_attn_workspace_bytes", "ttt_attn_fwd", "ttt_attn_bwd", "ttt_attn_last_error",
-           "ttt_attn_profile_enable", "ttt_attn_profile_totals")
+           "ttt_attn_profile_enable", "ttt_attn_profile_totals", "ttt_loss_bwd_inplace")
 
 
 class TttAttnParams(ctypes.Structure):
@@ -67,6 +67,9 @@ def load_library():
         lib.ttt_attn_profile_totals.restype = ctypes.c_int
         lib.ttt_attn_profile_totals.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_char_p),
                                                 ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32)]
+        lib.ttt_loss_bwd_inplace.restype = ctypes.c_int
+        lib.ttt_loss_bwd_inplace.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int64,
+                                             ctypes.c_int64, ctypes.c_int32, vp]
         _lib = lib
     return _lib
 
@@ -148,5 +151,21 @@ def ttt_attn_bwd(params, q, k, v, o, lse, d_o, cu_seqlens_dev, cu_seqlens_host, 
                           _ptr_array(dq, K), _ptr_array(dk, K), _ptr_array(dv, K), int(accumulate_dkv),
                           ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                           _stream_ptr(stream))
+    if rc != TTT_OK:
+        raise TttAttnError(rc, ttt_attn_last_error())
+
+
+def ttt_loss_bwd_inplace(logits, target, grad, stream=None):
+    """logits, target: [n_rows, vocab] device tensors of one dtype (fp32 or bf16), vocab contiguous;
+    grad: [n_rows] fp32.  Overwrites `logits` with the gradient of the loss (Alg. 3)."""
+    import torch
+    lib = load_library()
+    assert logits.dim() == 2 and target.shape == logits.shape and logits.dtype == target.dtype
+    assert logits.stride(1) == 1 and target.stride(1) == 1 and grad.dtype == torch.float32 and grad.is_contiguous()
+    dtype = {torch.float32: TTT_F32, torch.bfloat16: TTT_BF16}[logits.dtype]
+    n, v = logits.shape
+    rc = lib.ttt_loss_bwd_inplace(ctypes.c_void_p(logits.data_ptr()), ctypes.c_void_p(target.data_ptr()),
+                                  ctypes.c_void_p(grad.data_ptr()), n, v, logits.stride(0) if n > 1 else max(logits.stride(0), v),
+                                  target.stride(0) if n > 1 else max(target.stride(0), v), dtype, _stream_ptr(stream))
     if rc != TTT_OK:
         raise TttAttnError(rc, ttt_attn_last_error())

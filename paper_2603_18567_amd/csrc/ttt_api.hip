@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "../../include/ttt_attn.h"
+#include "../../include/ttt_loss.h"
 #include "ttt_args.hpp"
 
 namespace {
@@ -311,6 +312,25 @@ int ttt_attn_bwd(const ttt_attn_params* p, const void* const* q, const void* con
     }
     e = ttt::launch_bwd(p->dtype, p->head_dim, a, stream);
     if (e != hipSuccess) return fail(TTT_ERR_HIP, "backward kernel launch: %s", hipGetErrorString(e));
+    return TTT_OK;
+}
+
+int ttt_loss_bwd_inplace(void* logits, const void* target, const float* grad, int64_t n_rows, int32_t vocab,
+                         int64_t logits_row_stride, int64_t target_row_stride, int32_t dtype, void* hip_stream) {
+    if (dtype != TTT_F32 && dtype != TTT_BF16) return fail(TTT_ERR_UNSUPPORTED, "dtype %d is not TTT_F32/TTT_BF16", dtype);
+    if (n_rows < 0 || vocab < 1) return fail(TTT_ERR_INVALID_ARG, "n_rows=%lld must be >= 0 and vocab=%d >= 1", (long long)n_rows, vocab);
+    if (n_rows > 0x7fffffffLL) return fail(TTT_ERR_INVALID_ARG, "n_rows=%lld exceeds the grid limit", (long long)n_rows);
+    if (logits_row_stride < vocab || target_row_stride < vocab)
+        return fail(TTT_ERR_INVALID_ARG, "row strides (%lld, %lld) must be >= vocab=%d", (long long)logits_row_stride,
+                    (long long)target_row_stride, vocab);
+    if (n_rows == 0) return TTT_OK;
+    if (!logits || !target || !grad) return fail(TTT_ERR_INVALID_ARG, "logits, target or grad is NULL");
+    const uintptr_t esz = dtype == TTT_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(logits) % esz || reinterpret_cast<uintptr_t>(target) % esz || reinterpret_cast<uintptr_t>(grad) % 4)
+        return fail(TTT_ERR_INVALID_ARG, "a pointer is not aligned to its element size");
+    hipError_t e = ttt::launch_loss_bwd(dtype, logits, target, grad, n_rows, vocab, logits_row_stride, target_row_stride,
+                                        static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(TTT_ERR_HIP, "loss backward kernel launch: %s", hipGetErrorString(e));
     return TTT_OK;
 }
 

@@ -63,6 +63,8 @@ struct BwdArgs {
 hipError_t launch_tok_bounds(const int* cu_dev, int n_docs, int T, int* tok_start, int* tok_end, hipStream_t stream);
 hipError_t launch_fwd(int dtype, int head_dim, FwdArgs& a, hipStream_t stream);
 hipError_t launch_bwd(int dtype, int head_dim, BwdArgs& a, hipStream_t stream);
+hipError_t launch_loss_bwd(int dtype, void* logits, const void* target, const float* grad, int64_t n_rows, int vocab,
+                           int64_t logits_row_stride, int64_t target_row_stride, hipStream_t stream);
 
 // Diagnostics (off by default): brackets one kernel launch with HIP events on its stream so that
 // a caller can read per-kernel durations afterwards (ttt_attn_profile_totals).
