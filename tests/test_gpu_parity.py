@@ -40,6 +40,10 @@ SMALL = [
     custom_workload("bf16_k17", "bf16", [140], 2, 1, 128, 17, 17),                 # longest TTT length the paper studies
     custom_workload("bf16_sharp", "bf16", [400], 4, 2, 128, 3, 18, qk_mult=2.0),   # sharp softmax (long-context recipe)
     custom_workload("bf16_1100", "bf16", [700, 400], 16, 2, 128, 7, 19),           # several tiles in every kernel, G=8
+    custom_workload("bf16_k32_max", "bf16", [40], 2, 2, 128, 32, 20),              # the largest step count the ABI takes
+    custom_workload("bf16_hkv16", "bf16", [200, 120], 32, 16, 128, 2, 22),         # two kv heads per XCD in the block map
+    custom_workload("bf16_d64_multi", "bf16", [500, 333, 100], 8, 2, 64, 4, 23),   # head_dim 64 over several tiles
+    custom_workload("f32_multi_tile", "f32", [450, 310], 4, 2, 128, 3, 24),        # fp32 kernels over several tiles
 ]
 
 
