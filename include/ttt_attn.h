@@ -136,6 +136,29 @@ int ttt_attn_bwd(const ttt_attn_params* params,
                  int accumulate_dkv,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * The same two operations with a step count per document ("Impact of Training-Time Test" in the
+ * paper's Training Insights: the best TTT length depends on the task, and adjusting it per sample
+ * is named as the way forward).  doc_steps_host[r] in 0..k (HOST array, n_docs entries) is the number
+ * of TTT steps of document r: its tokens take part in steps j < doc_steps_host[r] only and own the
+ * cache blocks l < doc_steps_host[r] only.  For the other (step, document) combinations nothing is
+ * read and nothing is written: the rows of such a document in O_j, LSE_j, dQ_j, dK_l, dV_l keep
+ * their contents.  Documents are independent, so the call is carried out as one pass per run of
+ * consecutive documents with equal step count, one after the other on the stream, sharing the
+ * workspace (sized by ttt_attn_workspace_bytes for the whole batch as before); group documents by
+ * step count for the fewest passes.  The backward variant has no carry mode (accumulate_dkv = 0).
+ * All other arguments, layouts and errors are those of ttt_attn_fwd / ttt_attn_bwd.
+ */
+int ttt_attn_fwd_docsteps(const ttt_attn_params* params, const int32_t* doc_steps_host, const void* const* q,
+                          const void* const* k, const void* const* v, const int32_t* cu_seqlens_dev,
+                          const int32_t* cu_seqlens_host, void* const* o, float* const* lse, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+int ttt_attn_bwd_docsteps(const ttt_attn_params* params, const int32_t* doc_steps_host, const void* const* q,
+                          const void* const* k, const void* const* v, const void* const* o, const float* const* lse,
+                          const void* const* d_o, const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                          void* const* dq, void* const* dk, void* const* dv, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
 /* Message of the calling thread's most recent failing call ("" if none).  Never NULL. */
 const char* ttt_attn_last_error(void);
 

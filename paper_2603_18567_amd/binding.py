@@ -18,7 +18,8 @@ TTT_PASS_FWD, TTT_PASS_BWD, TTT_PASS_BWD_ACCUM = 0, 1, 2
 TTT_MAX_STEPS = 32
 
 EXPORTS = ("ttt_attn_workspace_bytes", "ttt_attn_fwd", "ttt_attn_bwd", "ttt_attn_last_error",
-           "ttt_attn_profile_enable", "ttt_attn_profile_totals", "ttt_loss_bwd_inplace")
+           "ttt_attn_profile_enable", "ttt_attn_profile_totals", "ttt_attn_fwd_docsteps", "ttt_attn_bwd_docsteps",
+           "ttt_loss_bwd_inplace")
 
 
 class TttAttnParams(ctypes.Structure):
@@ -60,6 +61,12 @@ def load_library():
         lib.ttt_attn_bwd.restype = ctypes.c_int
         lib.ttt_attn_bwd.argtypes = [ctypes.POINTER(TttAttnParams), pp, pp, pp, pp, pp, pp, vp, vp,
                                      pp, pp, pp, ctypes.c_int, vp, ctypes.c_size_t, vp]
+        lib.ttt_attn_fwd_docsteps.restype = ctypes.c_int
+        lib.ttt_attn_fwd_docsteps.argtypes = [ctypes.POINTER(TttAttnParams), vp, pp, pp, pp, vp, vp, pp, pp,
+                                              vp, ctypes.c_size_t, vp]
+        lib.ttt_attn_bwd_docsteps.restype = ctypes.c_int
+        lib.ttt_attn_bwd_docsteps.argtypes = [ctypes.POINTER(TttAttnParams), vp, pp, pp, pp, pp, pp, pp, vp, vp,
+                                              pp, pp, pp, vp, ctypes.c_size_t, vp]
         lib.ttt_attn_last_error.restype = ctypes.c_char_p
         lib.ttt_attn_last_error.argtypes = []
         lib.ttt_attn_profile_enable.restype = ctypes.c_int
@@ -137,6 +144,41 @@ def ttt_attn_fwd(params, q, k, v, cu_seqlens_dev, cu_seqlens_host, o, lse, works
                           _ptr_array(o, K), _ptr_array(lse, K),
                           ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                           _stream_ptr(stream))
+    if rc != TTT_OK:
+        raise TttAttnError(rc, ttt_attn_last_error())
+
+
+def _doc_steps_array(doc_steps, n_docs):
+    assert len(doc_steps) == n_docs
+    return (ctypes.c_int32 * max(n_docs, 1))(*[int(x) for x in doc_steps])
+
+
+def ttt_attn_fwd_docsteps(params, doc_steps, q, k, v, cu_seqlens_dev, cu_seqlens_host, o, lse, workspace, stream=None):
+    """ttt_attn_fwd with a step count per document (host list of n_docs integers in 0..k)."""
+    lib = load_library()
+    K = params.k
+    rc = lib.ttt_attn_fwd_docsteps(ctypes.byref(params), _doc_steps_array(doc_steps, params.n_docs),
+                                   _ptr_array(q, K), _ptr_array(k, K), _ptr_array(v, K),
+                                   ctypes.c_void_p(cu_seqlens_dev.data_ptr()), _cu_host_array(cu_seqlens_host),
+                                   _ptr_array(o, K), _ptr_array(lse, K),
+                                   ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                   _stream_ptr(stream))
+    if rc != TTT_OK:
+        raise TttAttnError(rc, ttt_attn_last_error())
+
+
+def ttt_attn_bwd_docsteps(params, doc_steps, q, k, v, o, lse, d_o, cu_seqlens_dev, cu_seqlens_host, dq, dk, dv,
+                          workspace, stream=None):
+    """ttt_attn_bwd (no carry mode) with a step count per document."""
+    lib = load_library()
+    K = params.k
+    rc = lib.ttt_attn_bwd_docsteps(ctypes.byref(params), _doc_steps_array(doc_steps, params.n_docs),
+                                   _ptr_array(q, K), _ptr_array(k, K), _ptr_array(v, K),
+                                   _ptr_array(o, K), _ptr_array(lse, K), _ptr_array(d_o, K),
+                                   ctypes.c_void_p(cu_seqlens_dev.data_ptr()), _cu_host_array(cu_seqlens_host),
+                                   _ptr_array(dq, K), _ptr_array(dk, K), _ptr_array(dv, K),
+                                   ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                   _stream_ptr(stream))
     if rc != TTT_OK:
         raise TttAttnError(rc, ttt_attn_last_error())
 

@@ -106,6 +106,7 @@ void fill_geometry(ttt::Geometry& g, const ttt_attn_params* p) {
     g.q_sh = p->q_stride_head;
     g.kv_st = p->kv_stride_token;
     g.kv_sh = p->kv_stride_head;
+    g.lse_st = p->total_tokens;
 }
 
 int check_workspace(const void* ws, size_t have, size_t need) {
@@ -201,9 +202,70 @@ size_t ttt_attn_workspace_bytes(const ttt_attn_params* params, int pass) {
     return make_layout(params, pass).total;
 }
 
-int ttt_attn_fwd(const ttt_attn_params* p, const void* const* q, const void* const* k, const void* const* v,
-                 const int32_t* cu_dev, const int32_t* cu_host, void* const* o, float* const* lse, void* workspace,
-                 size_t workspace_bytes, void* hip_stream) {
+// A slice of the batch: consecutive documents [doc0, doc0 + n_docs) = tokens [tok0, tok0 + tokens),
+// processed with the step range [step_begin, step_end).  The whole batch is one slice.
+struct Slice {
+    int doc0, n_docs, tok0, tokens, step_begin, step_end;
+};
+
+static int fwd_slice(const ttt_attn_params* p, const Slice& sl, const void* const* q, const void* const* k,
+                     const void* const* v, const int32_t* cu_dev, const int32_t* cu_host, void* const* o, float* const* lse,
+                     char* ws, hipStream_t stream) {
+    if (sl.tokens == 0 || sl.step_begin >= sl.step_end) return TTT_OK;
+    ttt_attn_params ps = *p;
+    ps.total_tokens = sl.tokens;
+    ps.n_docs = sl.n_docs;
+    ps.step_begin = sl.step_begin;
+    ps.step_end = sl.step_end;
+    const Layout L = make_layout(&ps, TTT_PASS_FWD);
+    int* tok_start = reinterpret_cast<int*>(ws + L.tok_start);
+    int* tok_end = reinterpret_cast<int*>(ws + L.tok_end);
+    hipError_t e = ttt::launch_tok_bounds(cu_dev + sl.doc0, cu_host[sl.doc0], sl.n_docs, sl.tokens, tok_start, tok_end, stream);
+    if (e != hipSuccess) return fail(TTT_ERR_HIP, "token-bounds kernel launch: %s", hipGetErrorString(e));
+
+    const size_t esz = p->dtype == TTT_F32 ? 4 : 2;
+    const size_t qoff = (size_t)sl.tok0 * (size_t)p->q_stride_token * esz;
+    const size_t kvoff = (size_t)sl.tok0 * (size_t)p->kv_stride_token * esz;
+    auto at = [](const void* base, size_t off) { return base ? static_cast<const char*>(base) + off : nullptr; };
+    ttt::FwdArgs a;
+    std::memset(&a, 0, sizeof(a));
+    fill_geometry(a.geo, &ps);
+    a.geo.lse_st = p->total_tokens;
+    for (int s = 0; s < p->k; ++s) {
+        a.q[s] = at(q[s], qoff);
+        a.k[s] = at(k[s], kvoff);
+        a.v[s] = at(v[s], kvoff);
+        a.o[s] = const_cast<char*>(at(o[s], qoff));
+        a.lse[s] = lse[s] ? lse[s] + sl.tok0 : nullptr;
+    }
+    a.tok_start = tok_start;
+    e = ttt::launch_fwd(p->dtype, p->head_dim, a, stream);
+    if (e != hipSuccess) return fail(TTT_ERR_HIP, "forward kernel launch: %s", hipGetErrorString(e));
+    return TTT_OK;
+}
+
+// Runs of consecutive documents with the same step count, as slices; steps beyond a document's own
+// count are cut off.  doc_steps == NULL: one slice with the call's step range.
+static int make_slices(const ttt_attn_params* p, const int32_t* cu_host, const int32_t* doc_steps, std::vector<Slice>& out) {
+    out.clear();
+    if (!doc_steps) {
+        out.push_back(Slice{0, p->n_docs, 0, p->total_tokens, p->step_begin, p->step_end});
+        return TTT_OK;
+    }
+    for (int r = 0; r < p->n_docs;) {
+        const int kr = doc_steps[r];
+        if (kr < 0 || kr > p->k) return fail(TTT_ERR_INVALID_ARG, "doc_steps[%d] = %d outside 0..k=%d", r, kr, p->k);
+        int r1 = r + 1;
+        while (r1 < p->n_docs && doc_steps[r1] == kr) ++r1;
+        out.push_back(Slice{r, r1 - r, cu_host[r], cu_host[r1] - cu_host[r], p->step_begin, kr < p->step_end ? kr : p->step_end});
+        r = r1;
+    }
+    return TTT_OK;
+}
+
+static int fwd_checked(const ttt_attn_params* p, const int32_t* doc_steps, const void* const* q, const void* const* k,
+                       const void* const* v, const int32_t* cu_dev, const int32_t* cu_host, void* const* o, float* const* lse,
+                       void* workspace, size_t workspace_bytes, void* hip_stream) {
     int rc = check_params(p);
     if (rc != TTT_OK) return rc;
     if (!q || !k || !v || !o || !lse) return fail(TTT_ERR_INVALID_ARG, "a step-pointer array is NULL");
@@ -221,34 +283,85 @@ int ttt_attn_fwd(const ttt_attn_params* p, const void* const* q, const void* con
     }
     const Layout L = make_layout(p, TTT_PASS_FWD);
     if ((rc = check_workspace(workspace, workspace_bytes, L.total)) != TTT_OK) return rc;
-
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    char* ws = static_cast<char*>(workspace);
-    int* tok_start = reinterpret_cast<int*>(ws + L.tok_start);
-    int* tok_end = reinterpret_cast<int*>(ws + L.tok_end);
-    hipError_t e = ttt::launch_tok_bounds(cu_dev, p->n_docs, p->total_tokens, tok_start, tok_end, stream);
-    if (e != hipSuccess) return fail(TTT_ERR_HIP, "token-bounds kernel launch: %s", hipGetErrorString(e));
-
-    ttt::FwdArgs a;
-    std::memset(&a, 0, sizeof(a));
-    fill_geometry(a.geo, p);
-    for (int s = 0; s < p->k; ++s) {
-        a.q[s] = q[s];
-        a.k[s] = k[s];
-        a.v[s] = v[s];
-        a.o[s] = o[s];
-        a.lse[s] = lse[s];
-    }
-    a.tok_start = tok_start;
-    e = ttt::launch_fwd(p->dtype, p->head_dim, a, stream);
-    if (e != hipSuccess) return fail(TTT_ERR_HIP, "forward kernel launch: %s", hipGetErrorString(e));
+    std::vector<Slice> slices;
+    if ((rc = make_slices(p, cu_host, doc_steps, slices)) != TTT_OK) return rc;
+    for (const Slice& sl : slices)   // slices run one after the other on the stream and share the workspace
+        if ((rc = fwd_slice(p, sl, q, k, v, cu_dev, cu_host, o, lse, static_cast<char*>(workspace),
+                            static_cast<hipStream_t>(hip_stream))) != TTT_OK)
+            return rc;
     return TTT_OK;
 }
 
-int ttt_attn_bwd(const ttt_attn_params* p, const void* const* q, const void* const* k, const void* const* v,
-                 const void* const* o, const float* const* lse, const void* const* d_o, const int32_t* cu_dev,
-                 const int32_t* cu_host, void* const* dq, void* const* dk, void* const* dv, int accumulate_dkv,
-                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+int ttt_attn_fwd(const ttt_attn_params* p, const void* const* q, const void* const* k, const void* const* v,
+                 const int32_t* cu_dev, const int32_t* cu_host, void* const* o, float* const* lse, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+    return fwd_checked(p, nullptr, q, k, v, cu_dev, cu_host, o, lse, workspace, workspace_bytes, hip_stream);
+}
+
+int ttt_attn_fwd_docsteps(const ttt_attn_params* p, const int32_t* doc_steps_host, const void* const* q, const void* const* k,
+                          const void* const* v, const int32_t* cu_dev, const int32_t* cu_host, void* const* o,
+                          float* const* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!doc_steps_host) return fail(TTT_ERR_INVALID_ARG, "doc_steps_host is NULL");
+    return fwd_checked(p, doc_steps_host, q, k, v, cu_dev, cu_host, o, lse, workspace, workspace_bytes, hip_stream);
+}
+
+static int bwd_slice(const ttt_attn_params* p, const Slice& sl, const void* const* q, const void* const* k,
+                     const void* const* v, const void* const* o, const float* const* lse, const void* const* d_o,
+                     const int32_t* cu_dev, const int32_t* cu_host, void* const* dq, void* const* dk, void* const* dv,
+                     int accumulate_dkv, char* ws, hipStream_t stream) {
+    if (sl.tokens == 0 || sl.step_begin >= sl.step_end) return TTT_OK;
+    ttt_attn_params ps = *p;
+    ps.total_tokens = sl.tokens;
+    ps.n_docs = sl.n_docs;
+    ps.step_begin = sl.step_begin;
+    ps.step_end = sl.step_end;
+    const int pass = accumulate_dkv ? TTT_PASS_BWD_ACCUM : TTT_PASS_BWD;
+    const Layout L = make_layout(&ps, pass);
+    int* tok_start = reinterpret_cast<int*>(ws + L.tok_start);
+    int* tok_end = reinterpret_cast<int*>(ws + L.tok_end);
+    hipError_t e = ttt::launch_tok_bounds(cu_dev + sl.doc0, cu_host[sl.doc0], sl.n_docs, sl.tokens, tok_start, tok_end, stream);
+    if (e != hipSuccess) return fail(TTT_ERR_HIP, "token-bounds kernel launch: %s", hipGetErrorString(e));
+
+    const size_t esz = p->dtype == TTT_F32 ? 4 : 2;
+    const size_t qoff = (size_t)sl.tok0 * (size_t)p->q_stride_token * esz;
+    const size_t kvoff = (size_t)sl.tok0 * (size_t)p->kv_stride_token * esz;
+    auto at = [](const void* base, size_t off) { return base ? static_cast<const char*>(base) + off : nullptr; };
+    ttt::BwdArgs a;
+    std::memset(&a, 0, sizeof(a));
+    fill_geometry(a.geo, &ps);
+    a.geo.lse_st = p->total_tokens;
+    for (int s = 0; s < p->k; ++s) {
+        a.q[s] = at(q[s], qoff);
+        a.k[s] = at(k[s], kvoff);
+        a.v[s] = at(v[s], kvoff);
+        a.o[s] = at(o[s], qoff);
+        a.lse[s] = lse[s] ? lse[s] + sl.tok0 : nullptr;
+        a.d_o[s] = at(d_o[s], qoff);
+        a.dq[s] = const_cast<char*>(at(dq[s], qoff));
+        a.dk[s] = const_cast<char*>(at(dk[s], kvoff));
+        a.dv[s] = const_cast<char*>(at(dv[s], kvoff));
+    }
+    a.tok_start = tok_start;
+    a.tok_end = tok_end;
+    a.delta = reinterpret_cast<float*>(ws + L.delta);
+    a.lse2 = reinterpret_cast<float*>(ws + L.lse2);
+    a.dk0_acc = reinterpret_cast<float*>(ws + L.dk0);
+    a.dv0_acc = reinterpret_cast<float*>(ws + L.dv0);
+    a.accumulate = accumulate_dkv;
+    a.carry_reset = accumulate_dkv && ps.step_end == p->k;
+    if (accumulate_dkv && p->k > 1) {
+        a.dkl_acc = reinterpret_cast<float*>(ws + L.dkl);
+        a.dvl_acc = reinterpret_cast<float*>(ws + L.dvl);
+    }
+    e = ttt::launch_bwd(p->dtype, p->head_dim, a, stream);
+    if (e != hipSuccess) return fail(TTT_ERR_HIP, "backward kernel launch: %s", hipGetErrorString(e));
+    return TTT_OK;
+}
+
+static int bwd_checked(const ttt_attn_params* p, const int32_t* doc_steps, const void* const* q, const void* const* k,
+                       const void* const* v, const void* const* o, const float* const* lse, const void* const* d_o,
+                       const int32_t* cu_dev, const int32_t* cu_host, void* const* dq, void* const* dk, void* const* dv,
+                       int accumulate_dkv, void* workspace, size_t workspace_bytes, void* hip_stream) {
     int rc = check_params(p);
     if (rc != TTT_OK) return rc;
     if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv) return fail(TTT_ERR_INVALID_ARG, "a step-pointer array is NULL");
@@ -276,43 +389,30 @@ int ttt_attn_bwd(const ttt_attn_params* p, const void* const* q, const void* con
     const int pass = accumulate_dkv ? TTT_PASS_BWD_ACCUM : TTT_PASS_BWD;
     const Layout L = make_layout(p, pass);
     if ((rc = check_workspace(workspace, workspace_bytes, L.total)) != TTT_OK) return rc;
-
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    char* ws = static_cast<char*>(workspace);
-    int* tok_start = reinterpret_cast<int*>(ws + L.tok_start);
-    int* tok_end = reinterpret_cast<int*>(ws + L.tok_end);
-    hipError_t e = ttt::launch_tok_bounds(cu_dev, p->n_docs, p->total_tokens, tok_start, tok_end, stream);
-    if (e != hipSuccess) return fail(TTT_ERR_HIP, "token-bounds kernel launch: %s", hipGetErrorString(e));
-
-    ttt::BwdArgs a;
-    std::memset(&a, 0, sizeof(a));
-    fill_geometry(a.geo, p);
-    for (int s = 0; s < p->k; ++s) {
-        a.q[s] = q[s];
-        a.k[s] = k[s];
-        a.v[s] = v[s];
-        a.o[s] = o[s];
-        a.lse[s] = lse[s];
-        a.d_o[s] = d_o[s];
-        a.dq[s] = dq[s];
-        a.dk[s] = dk[s];
-        a.dv[s] = dv[s];
-    }
-    a.tok_start = tok_start;
-    a.tok_end = tok_end;
-    a.delta = reinterpret_cast<float*>(ws + L.delta);
-    a.lse2 = reinterpret_cast<float*>(ws + L.lse2);
-    a.dk0_acc = reinterpret_cast<float*>(ws + L.dk0);
-    a.dv0_acc = reinterpret_cast<float*>(ws + L.dv0);
-    a.accumulate = accumulate_dkv;
-    a.carry_reset = accumulate_dkv && p->step_end == p->k;
-    if (accumulate_dkv && p->k > 1) {
-        a.dkl_acc = reinterpret_cast<float*>(ws + L.dkl);
-        a.dvl_acc = reinterpret_cast<float*>(ws + L.dvl);
-    }
-    e = ttt::launch_bwd(p->dtype, p->head_dim, a, stream);
-    if (e != hipSuccess) return fail(TTT_ERR_HIP, "backward kernel launch: %s", hipGetErrorString(e));
+    std::vector<Slice> slices;
+    if ((rc = make_slices(p, cu_host, doc_steps, slices)) != TTT_OK) return rc;
+    for (const Slice& sl : slices)
+        if ((rc = bwd_slice(p, sl, q, k, v, o, lse, d_o, cu_dev, cu_host, dq, dk, dv, accumulate_dkv,
+                            static_cast<char*>(workspace), static_cast<hipStream_t>(hip_stream))) != TTT_OK)
+            return rc;
     return TTT_OK;
+}
+
+int ttt_attn_bwd(const ttt_attn_params* p, const void* const* q, const void* const* k, const void* const* v,
+                 const void* const* o, const float* const* lse, const void* const* d_o, const int32_t* cu_dev,
+                 const int32_t* cu_host, void* const* dq, void* const* dk, void* const* dv, int accumulate_dkv,
+                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return bwd_checked(p, nullptr, q, k, v, o, lse, d_o, cu_dev, cu_host, dq, dk, dv, accumulate_dkv, workspace,
+                       workspace_bytes, hip_stream);
+}
+
+int ttt_attn_bwd_docsteps(const ttt_attn_params* p, const int32_t* doc_steps_host, const void* const* q,
+                          const void* const* k, const void* const* v, const void* const* o, const float* const* lse,
+                          const void* const* d_o, const int32_t* cu_dev, const int32_t* cu_host, void* const* dq,
+                          void* const* dk, void* const* dv, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!doc_steps_host) return fail(TTT_ERR_INVALID_ARG, "doc_steps_host is NULL");
+    return bwd_checked(p, doc_steps_host, q, k, v, o, lse, d_o, cu_dev, cu_host, dq, dk, dv, 0, workspace, workspace_bytes,
+                       hip_stream);
 }
 
 int ttt_loss_bwd_inplace(void* logits, const void* target, const float* grad, int64_t n_rows, int32_t vocab,

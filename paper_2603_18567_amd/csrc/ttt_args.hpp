@@ -19,6 +19,7 @@ struct Geometry {
     float scale_log2;    // softmax_scale * log2(e)
     int64_t q_st, q_sh;  // strides (elements) of Q/O/dO/dQ
     int64_t kv_st, kv_sh;
+    int64_t lse_st;      // row (head) stride of LSE_j in elements (the packed token count of the whole batch)
 };
 
 struct FwdArgs {
@@ -60,7 +61,7 @@ struct BwdArgs {
 };
 
 // launchers (defined in the kernel files); all enqueue on `stream` and return the launch status
-hipError_t launch_tok_bounds(const int* cu_dev, int n_docs, int T, int* tok_start, int* tok_end, hipStream_t stream);
+hipError_t launch_tok_bounds(const int* cu_dev, int base, int n_docs, int T, int* tok_start, int* tok_end, hipStream_t stream);
 hipError_t launch_fwd(int dtype, int head_dim, FwdArgs& a, hipStream_t stream);
 hipError_t launch_bwd(int dtype, int head_dim, BwdArgs& a, hipStream_t stream);
 hipError_t launch_loss_bwd(int dtype, void* logits, const void* target, const float* grad, int64_t n_rows, int vocab,

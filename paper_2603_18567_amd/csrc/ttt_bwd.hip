@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void ttt_bwd_pre_kernel(const BwdArgs a) {
                 if (valid) {
                     const int64_t at = ((int64_t)js * geo.hq + h) * Tn + i;
                     a.delta[at] = d;
-                    a.lse2[at] = a.lse[j][(int64_t)h * Tn + i] * kLog2e;
+                    a.lse2[at] = a.lse[j][(int64_t)h * geo.lse_st + i] * kLog2e;
                 }
             }
         }
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void ttt_bwd_pre_kernel(const BwdArgs a) {
                 }
                 s = group_sum<LPR>(s);
                 dp = group_sum<LPR>(dp);
-                const float lse = a.lse[j][(int64_t)h * Tn + i];
+                const float lse = a.lse[j][(int64_t)h * geo.lse_st + i];
                 const float p = fast_exp2((s * geo.scale - lse) * kLog2e);
                 const float ds = p * (dp - myD[(j - b) * G + hg]) * geo.scale;
 #pragma unroll
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(256) void ttt_bwd_pre_regs_kernel(const BwdArgs a) 
             const frag qf = gload_frag<T>(static_cast<const T*>(a.q[j]) + off);
             const frag go = gload_frag<T>(static_cast<const T*>(a.d_o[j]) + off);
             const frag oo = gload_frag<T>(static_cast<const T*>(a.o[j]) + off);
-            const float lse2 = a.lse[j][(int64_t)h * Tn + i] * kLog2e;
+            const float lse2 = a.lse[j][(int64_t)h * geo.lse_st + i] * kLog2e;
             const float dsum = group_sum_dpp<LPR>(dot8(go, oo, 0.f));
             if (sub == 0) {
                 const int64_t at = ((int64_t)js * geo.hq + h) * Tn + i;
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_kernel(const BwdArgs a) {
         qi[qb] = wq0 + 32 * qb + n;
         qc[qb] = qi[qb] < Tn ? qi[qb] : Tn - 1;
         st[qb] = a.tok_start[qc[qb]];
-        lse2[qb] = a.lse[j][(int64_t)h * Tn + qc[qb]] * kLog2e;
+        lse2[qb] = a.lse[j][(int64_t)h * geo.lse_st + qc[qb]] * kLog2e;
         dl[qb] = a.delta[((int64_t)js * geo.hq + h) * Tn + qc[qb]];
     }
     const int hi_w = min(wq0 + QB * 32 - 1, Tn - 1);
@@ -835,7 +835,7 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_kernel(const BwdArgs a) {
             const bool in = q < Tn;
             const int qq = in ? q : Tn - 1;
             // rows past the end get LSE = +inf so that p = 0
-            sLse(s)[tid] = in ? a.lse[j][(int64_t)h * Tn + qq] * kLog2e : INFINITY;
+            sLse(s)[tid] = in ? a.lse[j][(int64_t)h * geo.lse_st + qq] * kLog2e : INFINITY;
             sDl(s)[tid] = in ? a.delta[((int64_t)js * geo.hq + h) * Tn + qq] : 0.f;
             sSt(s)[tid] = a.tok_start[qq];
         }

@@ -259,7 +259,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
     for (int qb = 0; qb < QB; ++qb) {
         const float lt = half_sum(l[qb]);
         const float inv = 1.f / lt;
-        if (hh == 0 && qi[qb] < Tn) a.lse[j][(int64_t)h * Tn + qi[qb]] = m[qb] * geo.scale + __logf(lt);
+        if (hh == 0 && qi[qb] < Tn) a.lse[j][(int64_t)h * geo.lse_st + qi[qb]] = m[qb] * geo.scale + __logf(lt);
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -285,24 +285,26 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
 }
 
 // first / one-past-last token of each token's document, by binary search in cu_seqlens
-__global__ void ttt_tok_bounds_kernel(const int* __restrict__ cu, int n_docs, int T, int* __restrict__ tok_start,
+// (`cu` may be a slice of a longer cu_seqlens array: `base` = its first entry, subtracted so that
+// the bounds count from the slice's first token)
+__global__ void ttt_tok_bounds_kernel(const int* __restrict__ cu, int base, int n_docs, int T, int* __restrict__ tok_start,
                                       int* __restrict__ tok_end) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= T) return;
     int lo = 0, hi = n_docs;   // find the largest r with cu[r] <= i (then cu[r+1] > i)
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
-        if (cu[mid] <= i) lo = mid; else hi = mid;
+        if (cu[mid] - base <= i) lo = mid; else hi = mid;
     }
-    tok_start[i] = cu[lo];
-    tok_end[i] = cu[lo + 1];
+    tok_start[i] = cu[lo] - base;
+    tok_end[i] = cu[lo + 1] - base;
 }
 
-hipError_t launch_tok_bounds(const int* cu_dev, int n_docs, int T, int* tok_start, int* tok_end, hipStream_t stream) {
+hipError_t launch_tok_bounds(const int* cu_dev, int base, int n_docs, int T, int* tok_start, int* tok_end, hipStream_t stream) {
     if (T <= 0) return hipSuccess;
     ProfileScope prof("ttt_tok_bounds_kernel", stream);
-    hipLaunchKernelGGL(ttt_tok_bounds_kernel, dim3((T + 255) / 256), dim3(256), 0, stream, cu_dev, n_docs, T, tok_start,
-                       tok_end);
+    hipLaunchKernelGGL(ttt_tok_bounds_kernel, dim3((T + 255) / 256), dim3(256), 0, stream, cu_dev, base, n_docs, T,
+                       tok_start, tok_end);
     return hipGetLastError();
 }
 

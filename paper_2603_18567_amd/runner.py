@@ -38,6 +38,15 @@ class TttAttnRunner:
         B.ttt_attn_fwd(p, self.q, self.k, self.v, self.cu_dev, self.cu_host, self.o, self.lse,
                        self.workspace(B.TTT_PASS_FWD), stream)
 
+    def forward_docsteps(self, doc_steps, stream=None):
+        B.ttt_attn_fwd_docsteps(self.params(), doc_steps, self.q, self.k, self.v, self.cu_dev, self.cu_host, self.o,
+                                self.lse, self.workspace(B.TTT_PASS_FWD), stream)
+
+    def backward_docsteps(self, d_o, doc_steps, stream=None):
+        self.alloc_grads()
+        B.ttt_attn_bwd_docsteps(self.params(), doc_steps, self.q, self.k, self.v, self.o, self.lse, d_o, self.cu_dev,
+                                self.cu_host, self.dq, self.dk, self.dv, self.workspace(B.TTT_PASS_BWD), stream)
+
     def alloc_grads(self):
         if self.dq is None:
             self.dq = [torch.empty_like(x) for x in self.q]
