@@ -464,8 +464,8 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
     constexpr int STAGE_BYTES = 1 << 16;
     static_assert(2 * TILE_BYTES <= STAGE_BYTES, "stage layout");
     constexpr int NE = 2 * DB;   // matrix instructions of one dQ block update
-    constexpr int PDR = 3;
-    constexpr int PDT = 4 < NE ? 4 : NE;
+    constexpr int PDR = NW == 8 ? 2 : 3;
+    constexpr int PDT = NW == 8 ? 2 : (4 < NE ? 4 : NE);
     typedef __attribute__((address_space(3))) char lds_char;
 
     extern __shared__ __align__(16) char smem[];
@@ -712,17 +712,21 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
                 dv[t] = gload_frag<T>(vrow + t * 16 + hh * 8);
             }
         };
-        request(1);
+        // (with two waves per SIMD the other wave covers the load latency, and requesting one block
+        // ahead would not fit the registers)
+        constexpr bool kAhead = NW != 8;
+        if (kAhead) request(1);
         for (int lb = 1; lb <= j; ++lb) {
             float s = 0.f, dp = 0.f;
             uint32_t kk[DC][4];   // the key row in accumulator order, still packed
+            if (!kAhead) request(lb);
 #pragma unroll
             for (int t = 0; t < DC; ++t) {
                 s = dot8(qf[t], dk[t], s);
                 dp = dot8(gof[t], dv[t], dp);
             }
             frags_to_acc_order_packed<T, DC>(dk, kk);
-            if (lb < j) request(lb + 1);
+            if (kAhead && lb < j) request(lb + 1);
             s = half_sum(s);
             dp = half_sum(dp);
             const float p = fast_exp2(fmaf(s, c, -lse2));
@@ -1430,7 +1434,7 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
     // 3. dQ
     {
         constexpr bool kPipe = sizeof(T) == 2;
-        constexpr int NWQ = kPipe ? 4 : NW_DQ;
+        constexpr int NWQ = kPipe ? 8 : NW_DQ;
         constexpr int QT = NWQ * (kPipe ? 1 : QB_DQ) * 32;
         constexpr int LDS = kPipe ? 2 * (1 << 16) : 4 * 64 * D * (int)sizeof(T);
         const void* kern;
