@@ -11,7 +11,7 @@
 //                        operands and their dK, dV accumulators in registers while every
 //                        (step, head of the group, query tile at or below the diagonal) streams past
 //                        through LDS; partial sums of the (step, head) splits meet in fp32 atomics
-//                        (ttt_bwd_dkv_ws_kernel: wave-specialised variant for 16-bit types).
+//                        (ttt_bwd_dkv_p8_kernel: eight equal waves, for 16-bit types).
 //   ttt_bwd_finish_kernel  fp32 block-0 sums -> dK_0, dV_0 in the tensor dtype.
 #include "ttt_args.hpp"
 
@@ -952,54 +952,60 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_kernel(const BwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// dK_0, dV_0: key-stationary, wave-specialised (16-bit element types)
+// dK_0, dV_0: key-stationary, eight equal waves (16-bit element types)
 //
-// Measured on MI355X: vector instructions issued by the wave that also issues the matrix
-// instructions mostly serialise with them, while vector instructions of a SECOND wave on the same
-// SIMD hide in the matrix instructions' shadow.  So the eight waves of a workgroup form four pairs
-// (wave w and wave w+4 share a SIMD), each pair owning 32 of the workgroup's 128 key rows:
-//   score wave  (w):   S = Q K^T, dP = dO V^T for one block of 32 query rows (K_0, V_0 rows
-//                      stationary in registers), then P and dS on the vector ALU, written to LDS as
-//                      ready-made operand fragments.  The Q / dO fragments of the NEXT block are
-//                      requested from LDS before the vector work starts, so their latency (several
-//                      hundred cycles under load) is off the critical path;
-//   update wave (w+4): one block behind, reads those fragments and the transposed dO / Q fragments
-//                      and accumulates dV += P^T dO, dK += dS^T Q (accumulators in registers).  It
-//                      also requests the global -> LDS copies, four blocks ahead: it has the slack.
-// Both roles issue 16 matrix instructions per block; one workgroup barrier per block hands the
-// fragments over.  Query blocks (Q and dO rows) rotate through six LDS stages.
+// Measured on MI355X: a wave issues at most one instruction (of any kind) every ~8 cycles, so the
+// time of a step is close to 8 cycles x the instructions a wave executes in it, and the two waves of
+// a SIMD are worth most as two independent instruction streams doing the same work on different
+// data.  Hence: eight equal waves, and as few instructions per block as the arithmetic allows (stage
+// offsets as immediates in an unrolled pair of steps, pointers advanced instead of recomputed, LDS
+// reads and waits in pairs).  Workgroup = 128
+// key rows; wave w owns the 32 keys of pair w & 3 (fp32 dK, dV accumulators in registers) and takes
+// every second query block: group w >> 2 = parity of the block.  The K_0 / V_0 rows of the tile sit
+// in LDS for the whole tile (row-wise B operands of S = Q K^T and dP = dO V^T); query blocks (Q and
+// dO rows, LSE*log2e, D, document start) stream through a two-stage LDS ring, each group copying the
+// blocks it will use.  P and dS never leave the registers: the 16 accumulator values of a lane are
+// already two A-operand chunks of dV += P^T dO and dK += dS^T Q, whose B operands are read
+// transposed from the same stage.  One workgroup barrier per pair of blocks.  The two waves that
+// share a key range both add their partial sums to the fp32 accumulators in global memory.
 // ------------------------------------------------------------------------------------------------
-constexpr int kDkvStages = 6;
+template <typename T, int D> struct DkvP8 {
+    static constexpr int kKeys = 128;
+    static constexpr int kBlk = 32 * D * (int)sizeof(T);      // one 32-row block of one matrix
+    static constexpr int kSlot = 2 * kBlk;                    // Q block + dO block of one query block
+    static constexpr int kStage = 2 * kSlot;                  // one query block per wave group
+    static constexpr int kStages = 2;
+    static constexpr int kKBase = kStages * kStage;
+    static constexpr int kVBase = kKBase + kKeys * D * (int)sizeof(T);
+    static constexpr int kVecBase = kVBase + kKeys * D * (int)sizeof(T);
+    static constexpr int kVecSlot = 3 * 32 * 4;               // LSE*log2e, D, first token of the document
+    static constexpr int kVecStage = 2 * kVecSlot;
+    static constexpr int kLds = kVecBase + kStages * kVecStage;
+    static constexpr int kChunk = kKeys * 32;                 // 16 columns of all keys, operand-major
+};
 
 template <typename T, int D>
-__device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const int g, const int sp, const int tile) {
-    static_assert(sizeof(T) == 2, "wave-specialised dK/dV kernel is for 16-bit elements");
+__device__ __forceinline__ void dkv_p8_tile(const BwdArgs& a, char* smem, const int g, const int sp, const int tile) {
+    static_assert(sizeof(T) == 2, "this dK/dV kernel is for 16-bit elements");
     using E = Elem<T>;
     using frag = typename E::frag;
     using TL = Tile<T, D>;
-    constexpr int KVT = 128;                  // 4 pairs x 32 key rows
+    using C = DkvP8<T, D>;
+    constexpr int KVT = C::kKeys;
     constexpr int DC = D / 16;
     constexpr int DB = D / 32;
-    constexpr int NS = kDkvStages;            // LDS stages, one query block each
-    constexpr int AHEAD = NS - 2;             // a block is requested this many steps before the score waves' step
-    constexpr int BLK_BYTES = 32 * D * E::kBytes;
-    constexpr int STAGE_BYTES = 2 * BLK_BYTES;            // Q block, dO block
-    constexpr int VEC_BASE = NS * STAGE_BYTES;
-    constexpr int VEC_STAGE = 3 * 32 * 4;                 // LSE*log2e, D, first token of the document
-    constexpr int X_BASE = (VEC_BASE + NS * VEC_STAGE + 1023) & ~1023;
-    constexpr int X_SLOT = 4 * 1024;          // P^T (2 chunks) and dS^T (2 chunks), 1 KiB per fragment
-    constexpr int NE = 4 * DB;                // matrix instructions of an update wave per block
-    constexpr int PDT = NE < 10 ? NE : 10;    // transposed fragments requested ahead of their use
+    constexpr int NE = 4 * DB;                // dV / dK matrix instructions per block
+    constexpr int PDR = 2;                    // contraction chunks of S / dP requested ahead
+    constexpr int PDT = 4;                    // transposed fragments requested ahead
+    static_assert((C::kStage & (C::kStage - 1)) == 0, "the stage bit is toggled with XOR");
     typedef __attribute__((address_space(3))) char lds_char;
     typedef __attribute__((address_space(3))) frag lds_frag;
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
     const Geometry& geo = a.geo;
-
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int role = wave >> 2;               // 0: score wave, 1: update wave
-    const int pair = wave & 3;
+    const int pair = wave & 3, grp = wave >> 2;
     const int n = lane & 31, hh = lane >> 5;
     const int Tn = geo.T;
     const int kv_tile0 = tile * KVT;
@@ -1008,241 +1014,144 @@ __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const 
     const int wk_hi = min(wk0 + 31, Tn - 1);
     const int q_end = __builtin_amdgcn_readfirstlane(a.tok_end[min(kv_tile0 + KVT - 1, Tn - 1)]);
     const int wq_end = active ? __builtin_amdgcn_readfirstlane(a.tok_end[wk_hi]) : 0;
+    const bool wave_split = active && __builtin_amdgcn_readfirstlane(a.tok_start[wk_hi]) > wk0;
+    const int kvi = wk0 + n;
     const int qb_lo = kv_tile0 / 32;
     const int nqb = (q_end - 1) / 32 - qb_lo + 1;     // query blocks that see a key of this tile
     const int n_jh = geo.n_steps * geo.G;
     const int n_c = (n_jh - sp + a.n_split - 1) / a.n_split;
-    const int n_blk = n_c * nqb;              // blocks this workgroup streams
+    const int nqb2 = (nqb + 1) / 2;           // steps per (step, head) pair: one block per wave group
+    const int n_steps2 = n_c * nqb2;
     const float c = geo.scale_log2;
-    const uint32_t xa = lds0 + X_BASE + pair * (2 * X_SLOT) + lane * 16;   // this lane's place in slot 0
 
-    // Walks the block sequence without divisions: block b lives in LDS stage b % NS and is query
-    // block qb_lo + b % nqb of (step, head) pair number b / nqb of this workgroup's list.
-    struct Cursor {
-        int stage, qb, ci;
-        __device__ void next(int nqb_, int qb_lo_) {
-            if (++stage == NS) stage = 0;
-            if (++qb == qb_lo_ + nqb_) {
-                qb = qb_lo_;
-                ++ci;
-            }
+    // K_0, V_0 rows of the tile -> LDS
+    {
+        const T* K0 = static_cast<const T*>(a.k[0]) + (int64_t)g * geo.kv_sh;
+        const T* V0 = static_cast<const T*>(a.v[0]) + (int64_t)g * geo.kv_sh;
+        // operand-major layout [chunk of 16 columns][32-key pair][column half][key]: a lane's row
+        // fragment of chunk t is at (its own 16 bytes) + t * kChunk, so one address register serves
+        // all chunks of K and V, and consecutive lanes read consecutive 16-byte pieces
+        for (int u = wave; u < DC * 4; u += 8) {
+            const int t = u >> 2, rg = u & 3;
+            const int row = min(kv_tile0 + rg * 32 + n, Tn - 1);
+            const int64_t off = (int64_t)row * geo.kv_st + (2 * t + hh) * 8;
+            const uint32_t dst = lds0 + t * C::kChunk + rg * 1024;
+            async_copy16(K0 + off, dst + C::kKBase);
+            async_copy16(V0 + off, dst + C::kVBase);
         }
-    };
-    auto visible = [&](const Cursor& cur) {
-        const int q0 = cur.qb * 32;
-        return active && q0 + 31 >= wk0 && q0 < wq_end;
-    };
-
-    if (role == 0) {
-        // ================================ score waves ================================
-        uint32_t ra[DC];
-        {
-            LaneFrags<T, D> lf;
-            lf.init(lane);
-#pragma unroll
-            for (int t = 0; t < DC; ++t) ra[t] = lds0 + lf.row[t];
-        }
-        const uint32_t va0 = lds0 + VEC_BASE + hh * 16;
-        auto ld_row = [&](uint32_t sb, int which, int t) -> frag {
-            return *reinterpret_cast<const lds_frag*>((uintptr_t)(ra[t] + sb + which * BLK_BYTES));
-        };
-        auto ld_vec = [&](uint32_t vb, int which, int i4) -> f32x4 {
-            return *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(
-                (uintptr_t)(va0 + vb + which * 128 + i4 * 32));
-        };
-        // K_0, V_0 rows of the pair as stationary B operands
-        frag kf[DC], vf[DC];
-        {
-            const T* K0 = static_cast<const T*>(a.k[0]) + (int64_t)g * geo.kv_sh;
-            const T* V0 = static_cast<const T*>(a.v[0]) + (int64_t)g * geo.kv_sh;
-            const int kc = min(wk0 + n, Tn - 1);
-#pragma unroll
-            for (int t = 0; t < DC; ++t) {
-                kf[t] = gload_frag<T>(K0 + (int64_t)kc * geo.kv_st + t * 16 + hh * 8);
-                vf[t] = gload_frag<T>(V0 + (int64_t)kc * geo.kv_st + t * 16 + hh * 8);
-            }
-        }
-        const bool wave_split = active && __builtin_amdgcn_readfirstlane(a.tok_start[wk_hi]) > wk0;
-        const int kvi = wk0 + n;
-        __syncthreads();                 // blocks 0 .. AHEAD-1 have landed
-        __builtin_amdgcn_s_setprio(2);   // the score waves' matrix instructions go first: their vector
-                                         // work then runs while the update waves use the matrix core
-        Cursor cur{0, qb_lo, 0};
-        frag qa[DC], ga[DC];             // row fragments of the block about to be scored
-        if (n_blk > 0 && visible(cur)) {
-#pragma unroll
-            for (int t = 0; t < DC; ++t) {
-                qa[t] = ld_row(0, 0, t);
-                ga[t] = ld_row(0, 1, t);
-            }
-        }
-        for (int s = 0; s <= n_blk; ++s) {
-            Cursor nxt = cur;
-            nxt.next(nqb, qb_lo);
-            const bool fetch_next = s + 1 < n_blk && visible(nxt);
-            const uint32_t nsb = nxt.stage * STAGE_BYTES;
-            const bool vis = s < n_blk && visible(cur);
-            const uint32_t vb = cur.stage * VEC_STAGE;
-            const int q0 = cur.qb * 32;
-            f32x16 sacc, pacc;
-            f32x4 l4[4], d4[4];
-            if (vis) {
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    l4[i4] = ld_vec(vb, 0, i4);
-                    d4[i4] = ld_vec(vb, 1, i4);
-                }
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sacc[i] = pacc[i] = 0.f;
-#pragma unroll
-                for (int t = 0; t < DC; ++t) {
-                    sacc = mma(qa[t], kf[t], sacc);
-                    pacc = mma(ga[t], vf[t], pacc);
-                }
-            }
-            issue_fence();
-            if (fetch_next) {
-#pragma unroll
-                for (int t = 0; t < DC; ++t) {
-                    qa[t] = ld_row(nsb, 0, t);
-                    ga[t] = ld_row(nsb, 1, t);
-                }
-            }
-            issue_fence();
-            if (vis) {
-                // every row of the block sees every key of the pair iff the block lies at or below
-                // the pair's last key, ends before that key's document does, and the pair's keys are
-                // all in one document
-                const bool need_mask = q0 < wk0 + 31 || q0 + 31 >= wq_end || wave_split;
-                if (need_mask) {
-#pragma unroll
-                    for (int x = 0; x < 16; ++x) {
-                        const f32x4 s4 = ld_vec(vb, 2, x / 4);
-                        const int q = q0 + acc_row(x, hh);
-                        float p = fast_exp2(fmaf(sacc[x], c, -l4[x / 4][x % 4]));
-                        p = (kvi <= q && q < wq_end && kvi >= __float_as_int(s4[x % 4])) ? p : 0.f;
-                        sacc[x] = p;
-                        pacc[x] = p * (pacc[x] - d4[x / 4][x % 4]);
-                    }
-                } else {
-#pragma unroll
-                    for (int x = 0; x < 16; ++x) {
-                        const float p = fast_exp2(fmaf(sacc[x], c, -l4[x / 4][x % 4]));
-                        sacc[x] = p;
-                        pacc[x] = p * (pacc[x] - d4[x / 4][x % 4]);
-                    }
-                }
-                // hand P^T and dS^T over as operand fragments
-                const uint32_t xs = xa + (s & 1) * X_SLOT;
-#pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2) {
-                    *reinterpret_cast<lds_frag*>((uintptr_t)(xs + c2 * 1024)) = acc_chunk<T>(sacc, c2);
-                    *reinterpret_cast<lds_frag*>((uintptr_t)(xs + (2 + c2) * 1024)) = acc_chunk<T>(pacc, c2);
-                }
-            }
-            cur = nxt;
-            lds_barrier();   // fragments of block s are visible; slot and stage of block s-1 are free
-        }
-        return;
     }
 
-    // ================================ update waves: one block behind ================================
-    uint32_t ta[DB][2];
+    // per-lane LDS addresses: query-block fragments (this group's slot of stage 0), the pair's K rows
+    uint32_t ra[DC], ta[DB][2];
+    const uint32_t ka = lds0 + C::kKBase + pair * 1024 + lane * 16;
+    static_assert((DC - 1) * C::kChunk + C::kVBase - C::kKBase < 65536, "LDS offsets are 16-bit immediates");
     {
         LaneFrags<T, D> lf;
         lf.init(lane);
 #pragma unroll
+        for (int t = 0; t < DC; ++t) ra[t] = lds0 + lf.row[t] + grp * C::kSlot;
+#pragma unroll
         for (int db = 0; db < DB; ++db) {
-            ta[db][0] = lds0 + lf.tr[db][0];
-            ta[db][1] = lds0 + lf.tr[db][1];
+            ta[db][0] = lds0 + lf.tr[db][0] + grp * C::kSlot;
+            ta[db][1] = lds0 + lf.tr[db][1] + grp * C::kSlot;
         }
     }
-    auto ld_tr = [&](uint32_t sb, int which, int c2, int db) -> frag {
-        const uint32_t off = sb + which * BLK_BYTES + c2 * 16 * TL::kRowBytes;
+    const uint32_t va = lds0 + C::kVecBase + grp * C::kVecSlot + hh * 16;
+    auto ld = [&](uint32_t addr) -> frag { return *reinterpret_cast<const lds_frag*>((uintptr_t)addr); };
+    auto ld_tr = [&](uint32_t stage_off, int which, int c2, int db) -> frag {
+        const uint32_t off = stage_off + which * C::kBlk + c2 * 16 * TL::kRowBytes;
         union { s16x4 s[2]; frag v; } u;
         u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][0] + off));
         u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][1] + off));
         return u.v;
     };
+    auto ld_vec = [&](uint32_t off, int i4) -> f32x4 {
+        return *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>((uintptr_t)(va + off + i4 * 32));
+    };
 
-    // ---- copies: 32 x kPieces 16-byte pieces per matrix and block over the 256 update threads
+    // ---- copies: the 256 threads of a group copy the group's next block (32 x kPieces 16-byte
+    // pieces per matrix) and its three per-row vectors.  Group grp takes the query blocks
+    // qb_lo + 2 i + grp, i < nqb2, of one (step, head) pair after the other; if the number of blocks is
+    // odd, the last block of group 1 lies past every query that sees the tile and is skipped.
     constexpr int NLD = 32 * TL::kPieces / 256;
-    constexpr int PER = 2 * NLD;              // requests per block of waves 5..7; wave 4 adds 3
-    static_assert((AHEAD - 2) * (PER + 3) <= 21, "partial waits are written out up to 21 requests");
-    const int uw = wave - 4, ut = tid - 256;
-    // Per thread, once: where its pieces sit inside a block (byte offset from the block's first row;
-    // the host checks that 32 rows fit 32 bits).  Per block, only scalar work is left: a 64-bit
-    // base per matrix and the LDS destination.
-    int src_r[NLD], src_c[NLD];
+    const int gw = wave & 3, gt = tid & 255;
     uint32_t src_off[NLD];
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-        const int pidx = (i * 4 + uw) * 64 + lane;
+        const int pidx = (i * 4 + gw) * 64 + lane;
         const int r = pidx / TL::kPieces, pos = pidx % TL::kPieces;
-        src_r[i] = r;
-        src_c[i] = (pos ^ TL::swz(r)) * TL::kElemsPerPiece;
-        src_off[i] = (uint32_t)((r * geo.q_st + src_c[i]) * (int64_t)sizeof(T));
+        src_off[i] = (uint32_t)((r * geo.q_st + (pos ^ TL::swz(r)) * TL::kElemsPerPiece) * (int64_t)sizeof(T));
     }
     const uint32_t vec_off = (uint32_t)(lane & 31) * 4;
-    // Running state of the request stream: the (step, head) pair's base pointers change when the
-    // block sequence wraps around; from one block to the next only additions are left.
-    Cursor iss{0, qb_lo, 0};                  // next block to request
-    int iss_ci = -1;
-    const T *iss_q = nullptr, *iss_g = nullptr;           // row 0 of the pair's Q / dO
-    const float *iss_l = nullptr, *iss_d = nullptr;       // row 0 of the pair's LSE*log2e / D
-    const int64_t blk_step = 32 * geo.q_st;
-    const T *cur_q = nullptr, *cur_g = nullptr;           // first row of the next block
-    auto issue_next = [&]() {
-        if (iss.ci != iss_ci) {
-            iss_ci = iss.ci;
-            const int jh = sp + iss_ci * a.n_split;
-            const int js = jh / geo.G, h = g * geo.G + jh % geo.G;
-            const int j = geo.step_begin + js;
-            iss_q = static_cast<const T*>(a.q[j]) + (int64_t)h * geo.q_sh;
-            iss_g = static_cast<const T*>(a.d_o[j]) + (int64_t)h * geo.q_sh;
-            const int64_t at = ((int64_t)js * geo.hq + h) * Tn;
-            iss_l = a.lse2 + at;
-            iss_d = a.delta + at;
-            cur_q = iss_q + (int64_t)qb_lo * blk_step;
-            cur_g = iss_g + (int64_t)qb_lo * blk_step;
+    const uint32_t dst0 = __builtin_amdgcn_readfirstlane(lds0 + grp * C::kSlot + gw * 1024);
+    const uint32_t vdst0 = __builtin_amdgcn_readfirstlane(lds0 + C::kVecBase + grp * C::kVecSlot);
+    const int64_t blk2_stride = (int64_t)64 * geo.q_st;       // two blocks on, in elements
+    struct Pos {
+        int i, ci;             // block 2 i + grp of (step, head) pair number ci of this split
+        const T *q, *g;        // first row of the block in Q_j and dO_j of that head
+    };
+    const T *head_q = nullptr, *head_g = nullptr;             // of the pair the next request is in
+    const float *head_l = nullptr, *head_d = nullptr;
+    auto enter_pair = [&](Pos& ps) {
+        const int jh = sp + ps.ci * a.n_split;
+        const int js = jh / geo.G, h = g * geo.G + jh % geo.G;
+        const int j = geo.step_begin + js;
+        head_q = static_cast<const T*>(a.q[j]) + (int64_t)h * geo.q_sh;
+        head_g = static_cast<const T*>(a.d_o[j]) + (int64_t)h * geo.q_sh;
+        const int64_t at = ((int64_t)js * geo.hq + h) * Tn;
+        head_l = a.lse2 + at;
+        head_d = a.delta + at;
+        const int64_t first = (int64_t)(qb_lo + grp) * 32 * geo.q_st;
+        ps.q = head_q + first;
+        ps.g = head_g + first;
+    };
+    auto advance = [&](Pos& ps) {
+        if (++ps.i == nqb2) {
+            ps.i = 0;
+            ++ps.ci;
+            if (ps.ci < n_c) enter_pair(ps);
+        } else {
+            ps.q += blk2_stride;
+            ps.g += blk2_stride;
         }
-        const uint32_t st = lds0 + iss.stage * STAGE_BYTES;
-        const uint32_t vec = lds0 + VEC_BASE + iss.stage * VEC_STAGE;
-        const int row0 = iss.qb * 32;
+    };
+    auto request = [&](const Pos& ps, auto stage_c) {
+        constexpr int ST = decltype(stage_c)::value;
+        const uint32_t st = dst0 + ST * C::kStage;
+        const uint32_t vec = vdst0 + ST * C::kVecStage;
+        const int row0 = (qb_lo + 2 * ps.i + grp) * 32;
         if (row0 + 32 <= Tn) {
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
-                const int base = (i * 4 + uw) * 1024;
-                async_copy16(cur_q, src_off[i], st + base);
-                async_copy16(cur_g, src_off[i], st + BLK_BYTES + base);
+                async_copy16(ps.q, src_off[i], st + i * 4096);
+                async_copy16(ps.g, src_off[i], st + C::kBlk + i * 4096);
             }
-            if (ut < 32) {
-                async_copy4(iss_l + row0, vec_off, vec);
-                async_copy4(iss_d + row0, vec_off, vec + 128);
+            if (gt < 32) {
+                async_copy4(head_l + row0, vec_off, vec);
+                async_copy4(head_d + row0, vec_off, vec + 128);
                 async_copy4(a.tok_start + row0, vec_off, vec + 256);
             }
         } else {
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
-                const int row = min(row0 + src_r[i], Tn - 1);     // rows past the end are masked later
-                const int64_t off = (int64_t)row * geo.q_st + src_c[i];
-                const int base = (i * 4 + uw) * 1024;
-                async_copy16(iss_q + off, st + base);
-                async_copy16(iss_g + off, st + BLK_BYTES + base);
+                const int pidx = (i * 4 + gw) * 64 + lane;
+                const int r = pidx / TL::kPieces, pos = pidx % TL::kPieces;
+                const int row = min(row0 + r, Tn - 1);            // rows past the end are masked later
+                const int64_t off = (int64_t)row * geo.q_st + (pos ^ TL::swz(r)) * TL::kElemsPerPiece;
+                async_copy16(head_q + off, st + i * 4096);
+                async_copy16(head_g + off, st + C::kBlk + i * 4096);
             }
-            if (ut < 32) {
-                const int qq = min(row0 + ut, Tn - 1);
-                async_copy4(iss_l + qq, vec);
-                async_copy4(iss_d + qq, vec + 128);
+            if (gt < 32) {
+                const int qq = min(row0 + gt, Tn - 1);
+                async_copy4(head_l + qq, vec);
+                async_copy4(head_d + qq, vec + 128);
                 async_copy4(a.tok_start + qq, vec + 256);
             }
         }
-        cur_q += blk_step;
-        cur_g += blk_step;
-        iss.next(nqb, qb_lo);
     };
-#pragma unroll 1
-    for (int b = 0; b < AHEAD && b < n_blk; ++b) issue_next();
+    Pos nxt{0, 0, nullptr, nullptr};
+    enter_pair(nxt);
+    request(nxt, IntC<0>{});
 
     f32x16 dkacc[DB], dvacc[DB];
 #pragma unroll
@@ -1253,61 +1162,127 @@ __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const 
     wait_async_copies();
     __syncthreads();
 
-    // The transposed dO / Q fragments of a block do not depend on the score waves: the first PDT of
-    // them are requested one step early, before the barrier that publishes the block's P and dS.
-    // transposed fragment x = (c2 * DB + db) * 2 + (0: dO for dV, 1: Q for dK)
-    auto ld_tfr = [&](uint32_t sb, int x) -> frag { return ld_tr(sb, 1 - (x & 1), (x >> 1) / DB, (x >> 1) % DB); };
-    Cursor cur{0, qb_lo, 0};   // block s - 1 (after the advance below: block s)
-    frag tfr[NE];
-    for (int s = 0; s <= n_blk; ++s) {
-        // block s + AHEAD goes into the stage that block s - 2 left at the end of step s - 1
-        if (s + AHEAD < n_blk) issue_next();
-        if (s >= 1) {
-            if (visible(cur)) {
-                const uint32_t sb = cur.stage * STAGE_BYTES;
-                const uint32_t xs = xa + ((s - 1) & 1) * X_SLOT;
-                frag pfr[2], sfr[2];
+    // One step: request the blocks of the next step into the other stage, then this wave's block from
+    // stage ST (a compile-time constant, so that every LDS address is a register plus an immediate).
+    auto step = [&](const bool more, auto stage_c) {
+        constexpr int ST = decltype(stage_c)::value;
+        constexpr uint32_t SO = ST * C::kStage;
+        constexpr uint32_t VO = ST * C::kVecStage;
+        const int q0 = (qb_lo + 2 * nxt.i + grp) * 32;
+        if (more) {
+            advance(nxt);
+            request(nxt, IntC<1 - ST>{});
+        }
+        if (active && q0 + 31 >= wk0 && q0 < wq_end) {
+            // ---- S = Q K^T, dP = dO V^T for the pair's 32 keys, two contraction chunks at a time
+            f32x16 sacc, pacc;
+            {
+                frag qa[DC], kf[DC];
 #pragma unroll
-                for (int c2 = 0; c2 < 2; ++c2) {
-                    pfr[c2] = *reinterpret_cast<const lds_frag*>((uintptr_t)(xs + c2 * 1024));
-                    sfr[c2] = *reinterpret_cast<const lds_frag*>((uintptr_t)(xs + (2 + c2) * 1024));
+                for (int t = 0; t < 2; ++t) {
+                    qa[t] = ld(ra[t] + SO);
+                    kf[t] = ld(ka + t * C::kChunk);
                 }
 #pragma unroll
-                for (int x = 0; x < NE; ++x) {
-                    if (x + PDT < NE) tfr[x + PDT] = ld_tfr(sb, x + PDT);
+                for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+                for (int t = 0; t < DC; t += 2) {
+                    if (t + 2 < DC) {
+#pragma unroll
+                        for (int u = t + 2; u < t + 4; ++u) {
+                            qa[u] = ld(ra[u] + SO);
+                            kf[u] = ld(ka + u * C::kChunk);
+                        }
+                    }
                     issue_fence();
-                    const int c2 = (x >> 1) / DB, db = (x >> 1) % DB;
-                    if (x & 1) dkacc[db] = mma(sfr[c2], tfr[x], dkacc[db]);
-                    else       dvacc[db] = mma(pfr[c2], tfr[x], dvacc[db]);
+                    sacc = mma(qa[t], kf[t], sacc);
+                    sacc = mma(qa[t + 1], kf[t + 1], sacc);
                 }
             }
-            cur.next(nqb, qb_lo);
-        }
-        issue_fence();
-        if (s < n_blk && visible(cur)) {
-            const uint32_t sb = cur.stage * STAGE_BYTES;
+            {
+                frag ga[DC], vf[DC];
 #pragma unroll
-            for (int x = 0; x < PDT; ++x) tfr[x] = ld_tfr(sb, x);
-        }
-        // The score waves fetch block s + 2 right after this barrier (during step s + 1): it must
-        // have landed; the requests for the (up to two) blocks after it may stay in flight.
-        if (s + 2 < n_blk) {
-            // (a few explicit cases: the immediate of the wait instruction is a compile-time constant)
-            static_assert(AHEAD <= 5, "cases below");
-            const int newer = min(s + AHEAD, n_blk - 1) - (s + 2);
-            if (uw == 0) {
-                if (newer == AHEAD - 2) wait_copies_but(IntC<(AHEAD - 2) * (PER + 3)>{});
-                else if (newer == 2) wait_copies_but(IntC<2 * (PER + 3)>{});
-                else if (newer == 1) wait_copies_but(IntC<PER + 3>{});
-                else wait_async_copies();
-            } else {
-                if (newer == AHEAD - 2) wait_copies_but(IntC<(AHEAD - 2) * PER>{});
-                else if (newer == 2) wait_copies_but(IntC<2 * PER>{});
-                else if (newer == 1) wait_copies_but(IntC<PER>{});
-                else wait_async_copies();
+                for (int t = 0; t < 2; ++t) {
+                    ga[t] = ld(ra[t] + SO + C::kBlk);
+                    vf[t] = ld(ka + t * C::kChunk + (C::kVBase - C::kKBase));
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) pacc[i] = 0.f;
+#pragma unroll
+                for (int t = 0; t < DC; t += 2) {
+                    if (t + 2 < DC) {
+#pragma unroll
+                        for (int u = t + 2; u < t + 4; ++u) {
+                            ga[u] = ld(ra[u] + SO + C::kBlk);
+                            vf[u] = ld(ka + u * C::kChunk + (C::kVBase - C::kKBase));
+                        }
+                    }
+                    issue_fence();
+                    pacc = mma(ga[t], vf[t], pacc);
+                    pacc = mma(ga[t + 1], vf[t + 1], pacc);
+                }
+            }
+            // ---- P and dS.  Every row of the block sees every key of the pair iff the block lies at
+            // or below the pair's last key, ends before that key's document does, and the pair's keys
+            // are all in one document
+            const bool need_mask = q0 < wk0 + 31 || q0 + 31 >= wq_end || wave_split;
+            {
+                f32x4 l4[4];
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) l4[i4] = ld_vec(VO, i4);
+                if (need_mask) {
+                    f32x4 s4[4];
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) s4[i4] = ld_vec(VO + 256, i4);
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) {
+                        const int q = q0 + acc_row(x, hh);
+                        const float p = fast_exp2(fmaf(sacc[x], c, -l4[x / 4][x % 4]));
+                        const bool see = (kvi <= q) & (q < wq_end) & (kvi >= __float_as_int(s4[x / 4][x % 4]));
+                        sacc[x] = see ? p : 0.f;
+                    }
+                } else {
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) sacc[x] = fast_exp2(fmaf(sacc[x], c, -l4[x / 4][x % 4]));
+                }
+            }
+            issue_fence();
+            frag tfr[NE];
+#pragma unroll
+            for (int x = 0; x < 2; ++x) tfr[x] = ld_tr(SO, 1 - (x & 1), (x >> 1) / DB, (x >> 1) % DB);
+            {
+                f32x4 d4[4];
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) d4[i4] = ld_vec(VO + 128, i4);
+#pragma unroll
+                for (int x = 0; x < 16; ++x) pacc[x] = sacc[x] * (pacc[x] - d4[x / 4][x % 4]);
+            }
+            // ---- dV += P^T dO, dK += dS^T Q: the accumulator chunks are the A operands as they are
+            frag pfr[2], sfr[2];
+#pragma unroll
+            for (int c2 = 0; c2 < 2; ++c2) {
+                pfr[c2] = acc_chunk<T>(sacc, c2);
+                sfr[c2] = acc_chunk<T>(pacc, c2);
+            }
+            // transposed fragment x = (c2 * DB + db) * 2 + (0: dO for dV, 1: Q for dK), two at a time
+#pragma unroll
+            for (int x = 0; x < NE; x += 2) {
+                if (x + 2 < NE) {
+#pragma unroll
+                    for (int y = x + 2; y < x + 4; ++y) tfr[y] = ld_tr(SO, 1 - (y & 1), (y >> 1) / DB, (y >> 1) % DB);
+                }
+                issue_fence();
+                const int c2 = (x >> 1) / DB, db = (x >> 1) % DB;
+                dvacc[db] = mma(pfr[c2], tfr[x], dvacc[db]);
+                dkacc[db] = mma(sfr[c2], tfr[x + 1], dkacc[db]);
             }
         }
-        bare_barrier();   // the fragments requested above are not waited for here
+        wait_async_copies();
+        lds_barrier();   // the blocks of the next step are in LDS; everybody is done with those of this one
+    };
+    for (int s = 0; s < n_steps2; s += 2) {
+        step(s + 1 < n_steps2, IntC<0>{});
+        if (s + 1 < n_steps2) step(s + 2 < n_steps2, IntC<1>{});
     }
     if (!active) return;
 #pragma unroll
@@ -1328,18 +1303,18 @@ __device__ __forceinline__ void dkv_ws_tile(const BwdArgs& a, char* smem, const 
 // equal work, finish together, and the ones resident on an XCD keep streaming the same Q/dO tensors
 // (which then stay in that XCD's L2).
 template <typename T, int D>
-__global__ __launch_bounds__(512) void ttt_bwd_dkv_ws_kernel(const BwdArgs a) {
+__global__ __launch_bounds__(512) void ttt_bwd_dkv_p8_kernel(const BwdArgs a) {
     extern __shared__ __align__(16) char smem[];
     int g, rest;
     if (!decode_block(a.map, blockIdx.x, g, rest)) return;
     const int n_half = (a.n_tiles + 1) / 2;
     const int sp = rest / n_half;
     const int u = rest % n_half;
-    dkv_ws_tile<T, D>(a, smem, g, sp, u);
+    dkv_p8_tile<T, D>(a, smem, g, sp, u);
     const int mirror = a.n_tiles - 1 - u;
     if (mirror != u) {
         __syncthreads();
-        dkv_ws_tile<T, D>(a, smem, g, sp, mirror);
+        dkv_p8_tile<T, D>(a, smem, g, sp, mirror);
     }
 }
 
@@ -1462,12 +1437,12 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
 
     // 4. dK_0, dV_0
     {
-        constexpr bool kWs = sizeof(T) == 2;      // wave-specialised kernel for 16-bit types
+        constexpr bool kWs = sizeof(T) == 2;      // the eight-equal-waves kernel is for 16-bit types
         constexpr int KVT = kWs ? 128 : NW_KV * 32;
-        constexpr int WS_LDS = ((kDkvStages * 2 * 32 * D * 2 + kDkvStages * 3 * 32 * 4 + 1023) & ~1023) + 4 * 2 * 4096;
-        constexpr int LDS = kWs ? WS_LDS : 2 * (2 * 64 * D * (int)sizeof(T) + 3 * 64 * 4);
+        constexpr int P8_LDS = DkvP8<T, D>::kLds;
+        constexpr int LDS = kWs ? P8_LDS : 2 * (2 * 64 * D * (int)sizeof(T) + 3 * 64 * 4);
         const void* kern;
-        if constexpr (kWs) kern = (const void*)ttt_bwd_dkv_ws_kernel<T, D>;
+        if constexpr (kWs) kern = (const void*)ttt_bwd_dkv_p8_kernel<T, D>;
         else kern = (const void*)ttt_bwd_dkv_kernel<T, D, NW_KV>;
         static bool attr_done = false;
         if (!attr_done) {
@@ -1475,7 +1450,7 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
             if (e != hipSuccess) return e;
             attr_done = true;
         }
-        // the wave-specialised kernel addresses the rows of a 32-row block with 32-bit byte offsets
+        // that kernel addresses the rows of a 32-row block with 32-bit byte offsets
         if (kWs && geo.q_st * 32 * (int64_t)sizeof(T) >= (int64_t)1 << 32) return hipErrorInvalidValue;
         a.n_tiles = (geo.T + KVT - 1) / KVT;
         // split the (step, head) list of a kv tile so that the grid has a few thousand workgroups
@@ -1483,7 +1458,29 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         int n_split = 1;
         // units per kv head and split: key tiles, or mirrored pairs of key tiles
         const int n_units = kWs ? (a.n_tiles + 1) / 2 : a.n_tiles;
-        while (n_split < n_jh && (int64_t)n_units * geo.hkv * n_split < (kWs ? 1024 : 2048)) ++n_split;
+        if constexpr (kWs) {
+            // One workgroup fills a compute unit and costs about its number of (step, head) pairs (the
+            // mirrored tiles even out the rest), so the sweep takes rounds x pairs-per-workgroup, plus
+            // a start and a flush of the sums per round: take the split for which that is least.
+            static int n_cu = 0;
+            if (n_cu == 0) {
+                int dev = 0;
+                if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+                if ((e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+                if (n_cu <= 0) n_cu = 256;
+            }
+            double best = 0.;
+            for (int ns = 1; ns <= n_jh; ++ns) {
+                const int64_t wgs = (int64_t)n_units * geo.hkv * ns;
+                const double cost = (double)((wgs + n_cu - 1) / n_cu) * ((n_jh + ns - 1) / ns + 0.25);
+                if (ns == 1 || cost < best) {
+                    best = cost;
+                    n_split = ns;
+                }
+            }
+        } else {
+            while (n_split < n_jh && (int64_t)n_units * geo.hkv * n_split < 2048) ++n_split;
+        }
         a.n_split = n_split;
         int64_t grid;
         set_head_map(a.map, geo.hkv, n_units * n_split, grid);
@@ -1491,7 +1488,7 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         {
             ProfileScope prof("ttt_bwd_dkv_kernel", stream);
             if constexpr (kWs)
-                hipLaunchKernelGGL((ttt_bwd_dkv_ws_kernel<T, D>), dim3((unsigned)grid), dim3(512), LDS, stream, a);
+                hipLaunchKernelGGL((ttt_bwd_dkv_p8_kernel<T, D>), dim3((unsigned)grid), dim3(512), LDS, stream, a);
             else
                 hipLaunchKernelGGL((ttt_bwd_dkv_kernel<T, D, NW_KV>), dim3((unsigned)grid), dim3(NW_KV * 64), LDS, stream, a);
         }
