@@ -544,10 +544,18 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
         u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(ta[db][1] + off));
         return u.v;
     };
+    TileCopy<T, D, KT, NT> tile_copy;
+    tile_copy.init(geo.kv_st, tid);
     auto issue = [&](int u, int s) {
-        char* stg = smem + s * STAGE_BYTES;
-        tile_load_async<T, D, KT, NT>(stg, K0, geo.kv_st, u * KT, Tn - 1, tid);
-        tile_load_async<T, D, KT, NT>(stg + TILE_BYTES, V0, geo.kv_st, u * KT, Tn - 1, tid);
+        if ((u + 1) * KT <= Tn) {
+            const int64_t first = (int64_t)u * KT * geo.kv_st;
+            tile_copy.copy(lds0 + s * STAGE_BYTES, K0 + first);
+            tile_copy.copy(lds0 + s * STAGE_BYTES + TILE_BYTES, V0 + first);
+        } else {
+            char* stg = smem + s * STAGE_BYTES;
+            tile_load_async<T, D, KT, NT>(stg, K0, geo.kv_st, u * KT, Tn - 1, tid);
+            tile_load_async<T, D, KT, NT>(stg + TILE_BYTES, V0, geo.kv_st, u * KT, Tn - 1, tid);
+        }
     };
 
     issue(u_lo, 0);
@@ -1421,6 +1429,8 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
             if (e != hipSuccess) return e;
             attr_done = true;
         }
+        // the pipelined kernel addresses the pieces of up to 64 rows of K or V with 32-bit byte offsets
+        if (kPipe && geo.kv_st * 64 * (int64_t)sizeof(T) >= (int64_t)1 << 32) return hipErrorInvalidValue;
         a.n_tiles = (geo.T + QT - 1) / QT;
         int64_t grid;
         set_head_map(a.map, geo.hkv, a.n_tiles * geo.n_steps * geo.G, grid);

@@ -267,6 +267,37 @@ TTT_DEV void tile_load_async(char* tile, const T* g, int64_t stride_token, int r
     }
 }
 
+// The same copy for a tile all of whose rows exist, with the per-lane part of the source address
+// (row within the workgroup's pass, swizzled piece) worked out once.  One pass of the workgroup
+// covers kRowsPerIter rows, a multiple of 16, so the swizzle -- and with it the lane's offset from
+// the first row of the pass -- is the same in every pass: a tile costs kIters copy instructions and
+// as many wave-uniform pointer additions.  kRowsPerIter * stride_token * sizeof(T) must stay
+// below 2^32.
+template <typename T, int D, int ROWS, int NTHREADS>
+struct TileCopy {
+    using TL = Tile<T, D>;
+    static constexpr int kIters = ROWS * TL::kPieces / NTHREADS;
+    static constexpr int kRowsPerIter = NTHREADS / TL::kPieces;
+    static_assert(ROWS * TL::kPieces % NTHREADS == 0, "tile does not divide over the workgroup");
+    static_assert(NTHREADS % TL::kPieces == 0 && kRowsPerIter % 16 == 0, "the swizzle must repeat from pass to pass");
+    uint32_t off;           // bytes from the first element of a pass's first row to this lane's piece
+    uint32_t wave_dst;      // bytes from the start of a pass in the LDS tile to this wave's first piece
+    int64_t iter_stride;    // elements from one pass to the next
+    TTT_DEV void init(int64_t stride_token, int tid) {
+        const int wave = tid >> 6, lane = tid & 63;
+        const int p = wave * 64 + lane;
+        const int r = p / TL::kPieces, pos = p % TL::kPieces;
+        off = (uint32_t)((r * stride_token + (pos ^ TL::swz(r)) * TL::kElemsPerPiece) * (int64_t)sizeof(T));
+        wave_dst = __builtin_amdgcn_readfirstlane(wave * 1024);
+        iter_stride = kRowsPerIter * stride_token;
+    }
+    TTT_DEV void copy(uint32_t tile_lds, const T* first_row) const {
+#pragma unroll
+        for (int it = 0; it < kIters; ++it)
+            async_copy16(first_row + it * iter_stride, off, tile_lds + wave_dst + it * NTHREADS * 16);
+    }
+};
+
 // Workgroup barrier for data handed over through LDS only: this wave's LDS accesses are complete,
 // but its outstanding global-memory requests (copies into LDS stages that nobody reads yet) stay
 // in flight -- __syncthreads() would wait for them too.

@@ -12,6 +12,8 @@
 // Tiles are cut over the packed token axis, not per document: a row's visible prefix is
 // [tok_start[i], i], so a wave visits the kv tiles that intersect [tok_start[first row], last row]
 // and nothing else; tiles strictly inside that range for every row skip the mask code.
+#include <type_traits>
+
 #include "ttt_args.hpp"
 
 namespace ttt {
@@ -93,15 +95,31 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
     LaneFrags<T, D> lf;
     lf.init(lane);
 
+    // K_0 / V_0 rows of tile u -> stage s.  Tiles that lie inside the tensor (all but the last one)
+    // take the copy with precomputed lane offsets.
+    constexpr bool kFastCopy = sizeof(T) == 2;
+    struct NoCopy { TTT_DEV void init(int64_t, int) {} };
+    typename std::conditional<kFastCopy, TileCopy<T, D, KT, NT>, NoCopy>::type tile_copy;
+    tile_copy.init(geo.kv_st, tid);
+    auto load_tile = [&](int s, int u) {
+        if constexpr (kFastCopy) {
+            if ((u + 1) * KT <= Tn) {
+                const int64_t first = (int64_t)u * KT * geo.kv_st;
+                tile_copy.copy(lds_addr(sK(s)), K0 + first);
+                tile_copy.copy(lds_addr(sV(s)), V0 + first);
+                return;
+            }
+        }
+        tile_load_async<T, D, KT, NT>(sK(s), K0, geo.kv_st, u * KT, Tn - 1, tid);
+        tile_load_async<T, D, KT, NT>(sV(s), V0, geo.kv_st, u * KT, Tn - 1, tid);
+    };
+
     // one kv tile: wait for its copy, start the next one into the other stage, compute from this one
     auto step = [&](auto stage_c, int u) {
         constexpr int ST = decltype(stage_c)::value;
         wait_async_copies();
         __syncthreads();   // tile u is in LDS for everyone; everyone is done with the other stage
-        if (u < u_hi) {
-            tile_load_async<T, D, KT, NT>(sK(ST ^ 1), K0, geo.kv_st, (u + 1) * KT, Tn - 1, tid);
-            tile_load_async<T, D, KT, NT>(sV(ST ^ 1), V0, geo.kv_st, (u + 1) * KT, Tn - 1, tid);
-        }
+        if (u < u_hi) load_tile(ST ^ 1, u + 1);
         const int kv0 = u * KT;
         if (!(active && kv0 <= hi_w && kv0 + KT - 1 >= lo_w)) return;
         const char* tk = smem + ST * TILE_BYTES;
@@ -186,8 +204,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
         }
     };
 
-    tile_load_async<T, D, KT, NT>(sK(0), K0, geo.kv_st, u_lo * KT, Tn - 1, tid);
-    tile_load_async<T, D, KT, NT>(sV(0), V0, geo.kv_st, u_lo * KT, Tn - 1, tid);
+    load_tile(0, u_lo);
 
     // Diagonal keys of blocks 1..j (suffix part of the mask): one key per block and row, taken first
     // so that their global-memory latency overlaps the first tile copy.  Row-wise dot products on
@@ -340,6 +357,8 @@ template <typename T, int D, int QB, int NW, int MINB> static hipError_t launch_
     }
     if (grid <= 0) return hipSuccess;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    // the 16-bit kernels address the pieces of up to 64 rows of K or V with 32-bit byte offsets
+    if (sizeof(T) == 2 && geo.kv_st * 64 * (int64_t)sizeof(T) >= (int64_t)1 << 32) return hipErrorInvalidValue;
     ProfileScope prof("ttt_fwd_kernel", stream);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), C::kLds, stream, a);
     return hipGetLastError();
