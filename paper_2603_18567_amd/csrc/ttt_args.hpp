@@ -57,6 +57,8 @@ struct BwdArgs {
     int carry_reset;        // accumulate mode: this call starts the sweep (carry is overwritten, not read)
     int n_tiles;            // tiles of the kernel being launched
     int n_split;            // dK/dV kernel: ways the (step, head) list of one kv tile is split
+    int n_units;            // dK/dV kernel (16-bit): (key tile, query chunk) units per kv head and split
+    int chunk_blocks;       // dK/dV kernel (16-bit): 32-row query blocks per chunk (a multiple of 4)
     HeadMap map;
 };
 

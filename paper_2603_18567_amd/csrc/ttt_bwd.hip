@@ -993,7 +993,8 @@ template <typename T, int D> struct DkvP8 {
 };
 
 template <typename T, int D>
-__device__ __forceinline__ void dkv_p8_tile(const BwdArgs& a, char* smem, const int g, const int sp, const int tile) {
+__device__ __forceinline__ void dkv_p8_tile(const BwdArgs& a, char* smem, const int g, const int sp, const int tile,
+                                            const int chunk) {
     static_assert(sizeof(T) == 2, "this dK/dV kernel is for 16-bit elements");
     using E = Elem<T>;
     using frag = typename E::frag;
@@ -1003,8 +1004,6 @@ __device__ __forceinline__ void dkv_p8_tile(const BwdArgs& a, char* smem, const 
     constexpr int DC = D / 16;
     constexpr int DB = D / 32;
     constexpr int NE = 4 * DB;                // dV / dK matrix instructions per block
-    constexpr int PDR = 2;                    // contraction chunks of S / dP requested ahead
-    constexpr int PDT = 4;                    // transposed fragments requested ahead
     static_assert((C::kStage & (C::kStage - 1)) == 0, "the stage bit is toggled with XOR");
     typedef __attribute__((address_space(3))) char lds_char;
     typedef __attribute__((address_space(3))) frag lds_frag;
@@ -1024,8 +1023,11 @@ __device__ __forceinline__ void dkv_p8_tile(const BwdArgs& a, char* smem, const 
     const int wq_end = active ? __builtin_amdgcn_readfirstlane(a.tok_end[wk_hi]) : 0;
     const bool wave_split = active && __builtin_amdgcn_readfirstlane(a.tok_start[wk_hi]) > wk0;
     const int kvi = wk0 + n;
-    const int qb_lo = kv_tile0 / 32;
-    const int nqb = (q_end - 1) / 32 - qb_lo + 1;     // query blocks that see a key of this tile
+    // query blocks of this chunk that see a key of this tile
+    const int qb_lo = max(kv_tile0 / 32, chunk * a.chunk_blocks);
+    const int nqb = min((q_end - 1) / 32, (chunk + 1) * a.chunk_blocks - 1) - qb_lo + 1;
+    if (nqb <= 0) return;
+    const int wq_lim = min(wq_end, (qb_lo + nqb) * 32);   // blocks from here on are not this unit's
     const int n_jh = geo.n_steps * geo.G;
     const int n_c = (n_jh - sp + a.n_split - 1) / a.n_split;
     const int nqb2 = (nqb + 1) / 2;           // steps per (step, head) pair: one block per wave group
@@ -1079,8 +1081,11 @@ __device__ __forceinline__ void dkv_p8_tile(const BwdArgs& a, char* smem, const 
 
     // ---- copies: the 256 threads of a group copy the group's next block (32 x kPieces 16-byte
     // pieces per matrix) and its three per-row vectors.  Group grp takes the query blocks
-    // qb_lo + 2 i + grp, i < nqb2, of one (step, head) pair after the other; if the number of blocks is
-    // odd, the last block of group 1 lies past every query that sees the tile and is skipped.
+    // qb_lo + 2 nqb2 - 1 - grp - 2 i, i < nqb2, of one (step, head) pair after the other; if the number
+    // of blocks is odd, the first block of group 0 lies past every query that sees the tile and is
+    // skipped.  The sweep runs from the last query block down to the tile's own: all key tiles of a
+    // (kv head, split) start a pair at the same block, so the workgroups that share an XCD read the
+    // same Q / dO rows at about the same time and find them in its L2.
     constexpr int NLD = 32 * TL::kPieces / 256;
     const int gw = wave & 3, gt = tid & 255;
     uint32_t src_off[NLD];
@@ -1093,7 +1098,8 @@ __device__ __forceinline__ void dkv_p8_tile(const BwdArgs& a, char* smem, const 
     const uint32_t vec_off = (uint32_t)(lane & 31) * 4;
     const uint32_t dst0 = __builtin_amdgcn_readfirstlane(lds0 + grp * C::kSlot + gw * 1024);
     const uint32_t vdst0 = __builtin_amdgcn_readfirstlane(lds0 + C::kVecBase + grp * C::kVecSlot);
-    const int64_t blk2_stride = (int64_t)64 * geo.q_st;       // two blocks on, in elements
+    const int64_t blk2_stride = (int64_t)64 * geo.q_st;       // two blocks, in elements
+    const int qb_top = qb_lo + 2 * nqb2 - 1 - grp;            // this group's first block: the sweep runs downwards
     struct Pos {
         int i, ci;             // block 2 i + grp of (step, head) pair number ci of this split
         const T *q, *g;        // first row of the block in Q_j and dO_j of that head
@@ -1109,7 +1115,7 @@ __device__ __forceinline__ void dkv_p8_tile(const BwdArgs& a, char* smem, const 
         const int64_t at = ((int64_t)js * geo.hq + h) * Tn;
         head_l = a.lse2 + at;
         head_d = a.delta + at;
-        const int64_t first = (int64_t)(qb_lo + grp) * 32 * geo.q_st;
+        const int64_t first = (int64_t)qb_top * 32 * geo.q_st;
         ps.q = head_q + first;
         ps.g = head_g + first;
     };
@@ -1119,15 +1125,15 @@ __device__ __forceinline__ void dkv_p8_tile(const BwdArgs& a, char* smem, const 
             ++ps.ci;
             if (ps.ci < n_c) enter_pair(ps);
         } else {
-            ps.q += blk2_stride;
-            ps.g += blk2_stride;
+            ps.q -= blk2_stride;
+            ps.g -= blk2_stride;
         }
     };
     auto request = [&](const Pos& ps, auto stage_c) {
         constexpr int ST = decltype(stage_c)::value;
         const uint32_t st = dst0 + ST * C::kStage;
         const uint32_t vec = vdst0 + ST * C::kVecStage;
-        const int row0 = (qb_lo + 2 * ps.i + grp) * 32;
+        const int row0 = (qb_top - 2 * ps.i) * 32;
         if (row0 + 32 <= Tn) {
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
@@ -1176,12 +1182,12 @@ __device__ __forceinline__ void dkv_p8_tile(const BwdArgs& a, char* smem, const 
         constexpr int ST = decltype(stage_c)::value;
         constexpr uint32_t SO = ST * C::kStage;
         constexpr uint32_t VO = ST * C::kVecStage;
-        const int q0 = (qb_lo + 2 * nxt.i + grp) * 32;
+        const int q0 = (qb_top - 2 * nxt.i) * 32;
         if (more) {
             advance(nxt);
             request(nxt, IntC<1 - ST>{});
         }
-        if (active && q0 + 31 >= wk0 && q0 < wq_end) {
+        if (active && q0 + 31 >= wk0 && q0 < wq_lim) {
             // ---- S = Q K^T, dP = dO V^T for the pair's 32 keys, two contraction chunks at a time
             f32x16 sacc, pacc;
             {
@@ -1292,38 +1298,64 @@ __device__ __forceinline__ void dkv_p8_tile(const BwdArgs& a, char* smem, const 
         step(s + 1 < n_steps2, IntC<0>{});
         if (s + 1 < n_steps2) step(s + 2 < n_steps2, IntC<1>{});
     }
-    if (!active) return;
+    // The two waves of a key range first add their sums in LDS (the last barrier of the loop has
+    // freed all of it): half as many atomics.  Quad q of a lane's accumulators sits at
+    // (q * 256 + pair * 64 + lane) * 16 bytes.
+    static_assert(2 * DB * 4 * 256 * 16 <= C::kLds, "the sums of one wave group fit in LDS");
+    typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
+    const uint32_t sum_addr = lds0 + (pair * 64 + lane) * 16;
+    if (grp == 1) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                *(lds_f32x4*)(uintptr_t)(sum_addr + ((db * 4 + i4) * 2 + 0) * 4096) =
+                    f32x4{dkacc[db][4 * i4], dkacc[db][4 * i4 + 1], dkacc[db][4 * i4 + 2], dkacc[db][4 * i4 + 3]};
+                *(lds_f32x4*)(uintptr_t)(sum_addr + ((db * 4 + i4) * 2 + 1) * 4096) =
+                    f32x4{dvacc[db][4 * i4], dvacc[db][4 * i4 + 1], dvacc[db][4 * i4 + 2], dvacc[db][4 * i4 + 3]};
+            }
+    }
+    __syncthreads();
+    if (!active || grp == 1) return;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int kv = wk0 + acc_row(i, hh);
-            if (kv < Tn) {
-                const int64_t off = ((int64_t)kv * geo.hkv + g) * D + db * 32 + n;
-                atomicAdd(a.dk0_acc + off, dkacc[db][i]);
-                atomicAdd(a.dv0_acc + off, dvacc[db][i]);
+        for (int i4 = 0; i4 < 4; ++i4) {
+            const f32x4 k4 = *(const lds_f32x4*)(uintptr_t)(sum_addr + ((db * 4 + i4) * 2 + 0) * 4096);
+            const f32x4 v4 = *(const lds_f32x4*)(uintptr_t)(sum_addr + ((db * 4 + i4) * 2 + 1) * 4096);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = 4 * i4 + e;
+                const int kv = wk0 + acc_row(i, hh);
+                if (kv < Tn) {
+                    const int64_t off = ((int64_t)kv * geo.hkv + g) * D + db * 32 + n;
+                    atomicAdd(a.dk0_acc + off, dkacc[db][i] + k4[e]);
+                    atomicAdd(a.dv0_acc + off, dvacc[db][i] + v4[e]);
+                }
             }
         }
 }
 
-// One workgroup takes key tile u and its mirror n_tiles-1-u, one after the other: the two together
-// see the same number of query tiles whatever u is, so all workgroups of a (step, head) split carry
-// equal work, finish together, and the ones resident on an XCD keep streaming the same Q/dO tensors
-// (which then stay in that XCD's L2).
+// One workgroup = one key tile x one chunk of `chunk_blocks` query blocks x one split of the
+// (step, head) list of the kv head.  Units are numbered chunk by chunk, the tiles that a chunk can
+// see (those that begin at or before its last row) side by side: workgroups with consecutive numbers
+// stream the same Q / dO rows, (step, head) pair after pair, each pair costing all of them the same
+// number of blocks -- except the few tiles on the chunk's diagonal -- so they stay together and the
+// rows are read from HBM once per XCD, not once per workgroup.
 template <typename T, int D>
 __global__ __launch_bounds__(512) void ttt_bwd_dkv_p8_kernel(const BwdArgs a) {
     extern __shared__ __align__(16) char smem[];
     int g, rest;
     if (!decode_block(a.map, blockIdx.x, g, rest)) return;
-    const int n_half = (a.n_tiles + 1) / 2;
-    const int sp = rest / n_half;
-    const int u = rest % n_half;
-    dkv_p8_tile<T, D>(a, smem, g, sp, u);
-    const int mirror = a.n_tiles - 1 - u;
-    if (mirror != u) {
-        __syncthreads();
-        dkv_p8_tile<T, D>(a, smem, g, sp, mirror);
+    const int sp = rest / a.n_units;
+    int r = rest % a.n_units;
+    int chunk = 0;
+    for (;; ++chunk) {
+        const int tiles = min(a.n_tiles, (chunk + 1) * a.chunk_blocks / 4);   // 128-key tiles = 4 blocks
+        if (r < tiles) break;
+        r -= tiles;
     }
+    dkv_p8_tile<T, D>(a, smem, g, sp, r, chunk);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1463,15 +1495,22 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         // that kernel addresses the rows of a 32-row block with 32-bit byte offsets
         if (kWs && geo.q_st * 32 * (int64_t)sizeof(T) >= (int64_t)1 << 32) return hipErrorInvalidValue;
         a.n_tiles = (geo.T + KVT - 1) / KVT;
-        // split the (step, head) list of a kv tile so that the grid has a few thousand workgroups
+        // split the (step, head) list of a unit so that the grid fills the device evenly
         const int n_jh = geo.n_steps * geo.G;
         int n_split = 1;
-        // units per kv head and split: key tiles, or mirrored pairs of key tiles
-        const int n_units = kWs ? (a.n_tiles + 1) / 2 : a.n_tiles;
+        int n_units = a.n_tiles;   // units per kv head and split: key tiles, or (key tile, query chunk) pairs
         if constexpr (kWs) {
-            // One workgroup fills a compute unit and costs about its number of (step, head) pairs (the
-            // mirrored tiles even out the rest), so the sweep takes rounds x pairs-per-workgroup, plus
-            // a start and a flush of the sums per round: take the split for which that is least.
+            a.chunk_blocks = 16;
+            const int n_chunks = (geo.T + a.chunk_blocks * 32 - 1) / (a.chunk_blocks * 32);
+            n_units = 0;
+            for (int ch = 0; ch < n_chunks; ++ch) {
+                const int tiles = (ch + 1) * a.chunk_blocks / 4;
+                n_units += tiles < a.n_tiles ? tiles : a.n_tiles;
+            }
+            a.n_units = n_units;
+            // One workgroup fills a compute unit and costs about its number of (step, head) pairs, so the
+            // sweep takes rounds x pairs-per-workgroup, plus a start and a flush of the sums per round:
+            // take the split for which that is least.
             static int n_cu = 0;
             if (n_cu == 0) {
                 int dev = 0;
@@ -1482,7 +1521,7 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
             double best = 0.;
             for (int ns = 1; ns <= n_jh; ++ns) {
                 const int64_t wgs = (int64_t)n_units * geo.hkv * ns;
-                const double cost = (double)((wgs + n_cu - 1) / n_cu) * ((n_jh + ns - 1) / ns + 0.25);
+                const double cost = (double)((wgs + n_cu - 1) / n_cu) * ((n_jh + ns - 1) / ns + 0.5);
                 if (ns == 1 || cost < best) {
                     best = cost;
                     n_split = ns;
