@@ -19,7 +19,7 @@ TTT_MAX_STEPS = 32
 
 EXPORTS = ("ttt_attn_workspace_bytes", "ttt_attn_fwd", "ttt_attn_bwd", "ttt_attn_last_error",
            "ttt_attn_profile_enable", "ttt_attn_profile_totals", "ttt_attn_fwd_docsteps", "ttt_attn_bwd_docsteps",
-           "ttt_loss_bwd_inplace")
+           "ttt_loss_bwd_inplace", "ttt_qkv_rope_fwd")
 
 
 class TttAttnParams(ctypes.Structure):
@@ -77,6 +77,10 @@ def load_library():
         lib.ttt_loss_bwd_inplace.restype = ctypes.c_int
         lib.ttt_loss_bwd_inplace.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int64,
                                              ctypes.c_int64, ctypes.c_int32, vp]
+        lib.ttt_qkv_rope_fwd.restype = ctypes.c_int
+        lib.ttt_qkv_rope_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                         ctypes.c_int32, vp]
         _lib = lib
     return _lib
 
@@ -209,5 +213,27 @@ def ttt_loss_bwd_inplace(logits, target, grad, stream=None):
     rc = lib.ttt_loss_bwd_inplace(ctypes.c_void_p(logits.data_ptr()), ctypes.c_void_p(target.data_ptr()),
                                   ctypes.c_void_p(grad.data_ptr()), n, v, logits.stride(0) if n > 1 else max(logits.stride(0), v),
                                   target.stride(0) if n > 1 else max(target.stride(0), v), dtype, _stream_ptr(stream))
+    if rc != TTT_OK:
+        raise TttAttnError(rc, ttt_attn_last_error())
+
+
+def ttt_qkv_rope_fwd(x, w, cos_tab, sin_tab, pos, q, k, v, stream=None):
+    """x [T, Hin] and w [(hq + 2 hkv) d, Hin] bf16 (rows may be strided), cos_tab / sin_tab [n_pos, d/2] fp32,
+    pos [T] int32; writes q [T, hq, d], k [T, hkv, d], v [T, hkv, d] (bf16, contiguous)."""
+    import torch
+    lib = load_library()
+    T, hin = x.shape
+    hq, d = q.shape[1], q.shape[2]
+    hkv = k.shape[1]
+    assert x.dtype == w.dtype == q.dtype == k.dtype == v.dtype == torch.bfloat16
+    assert w.shape == ((hq + 2 * hkv) * d, hin) and x.stride(1) == 1 and w.stride(1) == 1
+    assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous() and k.shape == v.shape == (T, hkv, d)
+    assert cos_tab.dtype == sin_tab.dtype == torch.float32 and cos_tab.is_contiguous() and sin_tab.is_contiguous()
+    assert cos_tab.shape == sin_tab.shape and cos_tab.shape[1] == d // 2
+    assert pos.dtype == torch.int32 and pos.is_contiguous() and pos.numel() == T
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    rc = lib.ttt_qkv_rope_fwd(p(x), p(w), p(cos_tab), p(sin_tab), p(pos), p(q), p(k), p(v), T, hin, hq, hkv, d,
+                              x.stride(0) if T > 1 else max(x.stride(0), hin), w.stride(0), cos_tab.shape[0], TTT_BF16,
+                              _stream_ptr(stream))
     if rc != TTT_OK:
         raise TttAttnError(rc, ttt_attn_last_error())

@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_DIR = os.path.join(_HERE, "_lib")
 LIB_PATH = os.path.join(LIB_DIR, "libttt_attn.so")
-SOURCES = ("ttt_api.hip", "ttt_fwd.hip", "ttt_bwd.hip", "ttt_loss.hip")
+SOURCES = ("ttt_api.hip", "ttt_fwd.hip", "ttt_bwd.hip", "ttt_loss.hip", "ttt_qkv.hip")
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code generation

@@ -12,6 +12,7 @@
 
 #include "../../include/ttt_attn.h"
 #include "../../include/ttt_loss.h"
+#include "../../include/ttt_qkv.h"
 #include "ttt_args.hpp"
 
 namespace {
@@ -431,6 +432,30 @@ int ttt_loss_bwd_inplace(void* logits, const void* target, const float* grad, in
     hipError_t e = ttt::launch_loss_bwd(dtype, logits, target, grad, n_rows, vocab, logits_row_stride, target_row_stride,
                                         static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(TTT_ERR_HIP, "loss backward kernel launch: %s", hipGetErrorString(e));
+    return TTT_OK;
+}
+
+int ttt_qkv_rope_fwd(const void* x, const void* w, const float* cos_tab, const float* sin_tab, const int32_t* pos, void* q,
+                     void* k, void* v, int64_t tokens, int32_t hidden_in, int32_t hq, int32_t hkv, int32_t head_dim,
+                     int64_t x_row_stride, int64_t w_row_stride, int32_t n_pos, int32_t dtype, void* hip_stream) {
+    if (dtype != TTT_BF16) return fail(TTT_ERR_UNSUPPORTED, "dtype %d: the projection kernel is built for TTT_BF16", dtype);
+    if (head_dim != 128) return fail(TTT_ERR_UNSUPPORTED, "head_dim=%d: the projection kernel is built for 128", head_dim);
+    if (tokens < 0 || tokens > 0x7fffffffLL) return fail(TTT_ERR_INVALID_ARG, "tokens=%lld out of range", (long long)tokens);
+    if (hq < 1 || hkv < 1 || hq > 4096 || hkv > 4096) return fail(TTT_ERR_INVALID_ARG, "hq=%d, hkv=%d must be in [1, 4096]", hq, hkv);
+    if (hidden_in < 64 || hidden_in % 64) return fail(TTT_ERR_INVALID_ARG, "hidden_in=%d must be a positive multiple of 64", hidden_in);
+    if (n_pos < 1) return fail(TTT_ERR_INVALID_ARG, "n_pos=%d must be >= 1", n_pos);
+    if (x_row_stride < hidden_in || w_row_stride < hidden_in || x_row_stride % 8 || w_row_stride % 8)
+        return fail(TTT_ERR_INVALID_ARG, "row strides (%lld, %lld) must be multiples of 8 and >= hidden_in=%d",
+                    (long long)x_row_stride, (long long)w_row_stride, hidden_in);
+    if (tokens == 0) return TTT_OK;
+    if (!x || !w || !cos_tab || !sin_tab || !pos || !q || !k || !v) return fail(TTT_ERR_INVALID_ARG, "a pointer is NULL");
+    const void* ptrs[] = {x, w, cos_tab, sin_tab, q, k, v};
+    for (const void* ptr : ptrs)
+        if (reinterpret_cast<uintptr_t>(ptr) % 16) return fail(TTT_ERR_INVALID_ARG, "a tensor pointer is not 16-byte aligned");
+    if (reinterpret_cast<uintptr_t>(pos) % 4) return fail(TTT_ERR_INVALID_ARG, "pos is not 4-byte aligned");
+    hipError_t e = ttt::launch_qkv_rope(x, w, cos_tab, sin_tab, pos, q, k, v, tokens, hidden_in, hq, hkv, x_row_stride,
+                                        w_row_stride, n_pos, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(TTT_ERR_HIP, "projection kernel launch: %s", hipGetErrorString(e));
     return TTT_OK;
 }
 

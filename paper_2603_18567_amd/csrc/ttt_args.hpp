@@ -69,6 +69,10 @@ hipError_t launch_bwd(int dtype, int head_dim, BwdArgs& a, hipStream_t stream);
 hipError_t launch_loss_bwd(int dtype, void* logits, const void* target, const float* grad, int64_t n_rows, int vocab,
                            int64_t logits_row_stride, int64_t target_row_stride, hipStream_t stream);
 
+hipError_t launch_qkv_rope(const void* x, const void* w, const float* cos_tab, const float* sin_tab, const int* pos, void* q,
+                           void* k, void* v, int64_t tokens, int hidden_in, int hq, int hkv, int64_t x_st, int64_t w_st,
+                           int n_pos, hipStream_t stream);
+
 // Diagnostics (off by default): brackets one kernel launch with HIP events on its stream so that
 // a caller can read per-kernel durations afterwards (ttt_attn_profile_totals).
 void profile_begin(const char* kernel_name, hipStream_t stream);
