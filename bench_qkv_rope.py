@@ -100,7 +100,10 @@ def main():
            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": f"draft_qkv_{T}x{hin}x{nf}", "tokens": T, "hidden_in": hin, "hq": hq, "hkv": hkv, "head_dim": d},
            "roofline": {"kernel": "ttt_qkv_rope_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": ach / PEAK_TFLOPS if ach else None, "traffic": None, "avg_ms": k_ms,
+                        "frac": ach / PEAK_TFLOPS if ach else None,
+                        # recorded from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of the default command
+                        # (profiles/qkv_rope_4096x8192x6144_kernel_stats.txt)
+                        "traffic": 628.9e6 + 97.6e6 if (T, hin, hq, hkv) == (4096, 8192, 32, 8) else None, "avg_ms": k_ms,
                         "algorithmic_flops_per_launch": flops},
            "unfused_comparison": {"vendor_gemm_plus_rotation_ms": unf_ms, "vendor_gemm_alone_ms": gemm_ms,
                                   "vendor_gemm_alone_tflops": flops / (gemm_ms * 1e-3) / 1e12,
