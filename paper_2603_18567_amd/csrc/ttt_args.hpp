@@ -31,6 +31,7 @@ struct FwdArgs {
     float* lse[kMaxSteps];
     const int* tok_start;   // [T] first token of each token's document
     int n_tiles;            // query tiles over the packed token axis
+    int pack_log2;          // log2 of the query heads (of one kv group) that share a workgroup
     HeadMap map;
 };
 

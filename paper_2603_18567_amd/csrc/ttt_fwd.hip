@@ -39,17 +39,23 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
     const Geometry& geo = a.geo;
     int g, rest;
     if (!decode_block(a.map, blockIdx.x, g, rest)) return;
-    const int hg = rest % geo.G;
-    rest /= geo.G;
+    // The waves of a workgroup are 2^pack_log2 query heads of the kv group x NW >> pack_log2 blocks of
+    // rows: heads that share K_0 / V_0 also share the key range, so all waves of a workgroup see
+    // (almost) the same number of key tiles and none idles while the tile on the diagonal is finished.
+    const int pk = a.pack_log2;
+    const int n_hgrp = geo.G >> pk;
+    const int hgrp = rest % n_hgrp;
+    rest /= n_hgrp;
     const int j = geo.step_begin + rest % geo.n_steps;
     const int tile = a.n_tiles - 1 - rest / geo.n_steps;   // long-prefix tiles first
-    const int h = g * geo.G + hg;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int h = g * geo.G + (hgrp << pk) + (wave & ((1 << pk) - 1));
     const int n = lane & 31, hh = lane >> 5;
     const int Tn = geo.T;   // packed tokens
-    const int q_tile0 = tile * QT;
-    const int wq0 = q_tile0 + wave * (QB * 32);
+    const int qt_rows = QT >> pk;   // rows of a workgroup
+    const int q_tile0 = tile * qt_rows;
+    const int wq0 = q_tile0 + (wave >> pk) * (QB * 32);
     const bool active = wq0 < Tn;
 
     const T* Qj = static_cast<const T*>(a.q[j]) + (int64_t)h * geo.q_sh;
@@ -68,7 +74,7 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
     const int lo_w = active ? __builtin_amdgcn_readfirstlane(a.tok_start[min(wq0, Tn - 1)]) : 0;
     const int st_hi = active ? __builtin_amdgcn_readfirstlane(a.tok_start[hi_w]) : 0;
     const int lo = __builtin_amdgcn_readfirstlane(a.tok_start[q_tile0]);
-    const int hi = min(q_tile0 + QT - 1, Tn - 1);
+    const int hi = min(q_tile0 + qt_rows - 1, Tn - 1);
     const int u_lo = lo / KT, u_hi = hi / KT;
 
     // Q as the stationary B operand: lane (n,hh) holds Q[row n][16t + 8hh .. +8]
@@ -340,9 +346,14 @@ template <typename T, int D, int QB, int NW, int MINB> static hipError_t launch_
         attr_done = true;
     }
     const Geometry& geo = a.geo;
-    a.n_tiles = (geo.T + C::kQT - 1) / C::kQT;
+    // as many heads of a kv group per workgroup as divide both the group and the waves (at most 4:
+    // a workgroup keeps at least 64 rows)
+    a.pack_log2 = 0;
+    while ((2 << a.pack_log2) <= 4 && geo.G % (2 << a.pack_log2) == 0 && NW % (2 << a.pack_log2) == 0) ++a.pack_log2;
+    const int qt_rows = C::kQT >> a.pack_log2;
+    a.n_tiles = (geo.T + qt_rows - 1) / qt_rows;
     a.map.hkv = geo.hkv;
-    a.map.rest_count = a.n_tiles * geo.n_steps * geo.G;
+    a.map.rest_count = a.n_tiles * geo.n_steps * (geo.G >> a.pack_log2);
     int64_t grid;
     if (geo.hkv % 8 == 0) {
         a.map.mode = 1;
