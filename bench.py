@@ -79,8 +79,8 @@ def cpu_baseline(wl, inp, rows_override=0, target_s=15.0):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path needs no collective; see DESIGN.md "
-              "for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path needs no collective: documents, heads "
+              "and steps are independent). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2603_18567_amd import TttAttnRunner, binding
