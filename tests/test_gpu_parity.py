@@ -44,6 +44,7 @@ SMALL = [
     custom_workload("bf16_hkv16", "bf16", [200, 120], 32, 16, 128, 2, 22),         # two kv heads per XCD in the block map
     custom_workload("bf16_d64_multi", "bf16", [500, 333, 100], 8, 2, 64, 4, 23),   # head_dim 64 over several tiles
     custom_workload("f32_multi_tile", "f32", [450, 310], 4, 2, 128, 3, 24),        # fp32 kernels over several tiles
+    custom_workload("bf16_gqa3", "bf16", [300, 45, 600], 6, 2, 128, 3, 25),        # 3 query heads per kv head: no head packing
 ]
 
 
