@@ -43,3 +43,13 @@ def qkv_rope(x, w, cos_tab, sin_tab, pos, hq, hkv, d):
         return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
 
     return rot(y[:, :hq]), rot(y[:, hq:hq + hkv]), y[:, hq + hkv:].copy()
+
+
+def o_proj(o, w):
+    """The consumer on the other side of the attention: out[t, f] = sum_c o[t, c] * w[f, c], with o the
+    attention output [T, hq, d] (or already [T, hq * d]) and w [out_features, hq * d]; fp64."""
+    o = np.asarray(o, dtype=np.float64)
+    o = o.reshape(o.shape[0], -1)
+    w = np.asarray(w, dtype=np.float64)
+    assert w.shape[1] == o.shape[1]
+    return o @ w.T

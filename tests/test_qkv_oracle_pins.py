@@ -83,3 +83,19 @@ def test_scores_depend_on_the_position_difference_only():
     np.testing.assert_allclose(score(17, 5), score(112, 100), rtol=1e-12)
     np.testing.assert_allclose(score(3, 3), score(150, 150), rtol=1e-12)
     assert abs(score(17, 5) - score(17, 6)) > 1e-6   # and it does depend on that difference
+
+
+def test_output_projection_is_the_plain_product_exact_in_integers():
+    from oracle.qkv_oracle import o_proj
+    rng = np.random.default_rng(8)
+    T, hq, d, nout = 4, 2, 3, 5
+    o = rng.integers(-5, 6, (T, hq, d))
+    w = rng.integers(-5, 6, (nout, hq * d))
+    want = np.zeros((T, nout), dtype=np.int64)
+    for t in range(T):
+        for f in range(nout):
+            want[t, f] = sum(int(o[t, h, i]) * int(w[f, h * d + i]) for h in range(hq) for i in range(d))
+    assert np.array_equal(o_proj(o, w), want.astype(np.float64))
+    # heads are concatenated in order: a weight that picks element (h, i) returns it
+    pick = np.zeros((1, hq * d)); pick[0, 1 * d + 2] = 1.0
+    assert np.array_equal(o_proj(o, pick)[:, 0], o[:, 1, 2].astype(np.float64))
