@@ -108,6 +108,12 @@ def main():
            "unfused_comparison": {"vendor_gemm_plus_rotation_ms": unf_ms, "vendor_gemm_alone_ms": gemm_ms,
                                   "vendor_gemm_alone_tflops": flops / (gemm_ms * 1e-3) / 1e12,
                                   "max_abs_diff_to_ours": diff}}
+    # the consumer: output projection reading O_j ([T, hq * d] -> hidden = hq * d), same kernel, no rotation
+    wo = (torch.randn(hq * d, hq * d, generator=gen, device=dev) / math.sqrt(hq * d)).to(torch.bfloat16)
+    proj = torch.empty(T, hq * d, dtype=torch.bfloat16, device=dev)
+    o_ms = timed(lambda: B.ttt_o_proj_fwd(q, wo, proj))
+    out["o_projection"] = {"ms": o_ms, "tflops": 2.0 * T * (hq * d) ** 2 / (o_ms * 1e-3) / 1e12,
+                           "vendor_gemm_ms": timed(lambda: torch.matmul(q.view(T, -1), wo.t()))}
     if not args.no_cpu_baseline:
         from oracle.qkv_oracle import qkv_rope
         n = min(T, 256)

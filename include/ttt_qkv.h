@@ -44,6 +44,21 @@ int ttt_qkv_rope_fwd(const void* x, const void* w, const float* cos_tab, const f
                      void* k, void* v, int64_t tokens, int32_t hidden_in, int32_t hq, int32_t hkv, int32_t head_dim,
                      int64_t x_row_stride, int64_t w_row_stride, int32_t n_pos, int32_t dtype, void* hip_stream);
 
+/*
+ * The consumer on the other side of the attention: the output projection that reads O_j as the
+ * attention kernels wrote it ([tokens, hq * head_dim] is [tokens, hq, head_dim] seen as a matrix):
+ *     out[t, f] = sum_c o[t, c] * w[f, c]
+ * Same kernel as above without the rotation (the paper names no fusion on this side; the call exists
+ * so that the attention block of the draft layer can be driven through this library alone).
+ *   o   [tokens, in_features]        bf16, row stride o_row_stride elements (multiple of 8)
+ *   w   [out_features, in_features]  bf16, row stride w_row_stride (multiple of 8)
+ *   out [tokens, out_features]       bf16, contiguous, fully overwritten
+ *   in_features a multiple of 64, out_features a multiple of 128; dtype = TTT_BF16.
+ * Memory, stream and error conventions as for ttt_qkv_rope_fwd.
+ */
+int ttt_o_proj_fwd(const void* o, const void* w, void* out, int64_t tokens, int32_t in_features, int32_t out_features,
+                   int64_t o_row_stride, int64_t w_row_stride, int32_t dtype, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,7 @@ TTT_MAX_STEPS = 32
 
 EXPORTS = ("ttt_attn_workspace_bytes", "ttt_attn_fwd", "ttt_attn_bwd", "ttt_attn_last_error",
            "ttt_attn_profile_enable", "ttt_attn_profile_totals", "ttt_attn_fwd_docsteps", "ttt_attn_bwd_docsteps",
-           "ttt_loss_bwd_inplace", "ttt_qkv_rope_fwd")
+           "ttt_loss_bwd_inplace", "ttt_qkv_rope_fwd", "ttt_o_proj_fwd")
 
 
 class TttAttnParams(ctypes.Structure):
@@ -81,6 +81,9 @@ def load_library():
         lib.ttt_qkv_rope_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
                                          ctypes.c_int32, vp]
+        lib.ttt_o_proj_fwd.restype = ctypes.c_int
+        lib.ttt_o_proj_fwd.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
+                                       ctypes.c_int64, ctypes.c_int32, vp]
         _lib = lib
     return _lib
 
@@ -235,5 +238,20 @@ def ttt_qkv_rope_fwd(x, w, cos_tab, sin_tab, pos, q, k, v, stream=None):
     rc = lib.ttt_qkv_rope_fwd(p(x), p(w), p(cos_tab), p(sin_tab), p(pos), p(q), p(k), p(v), T, hin, hq, hkv, d,
                               x.stride(0) if T > 1 else max(x.stride(0), hin), w.stride(0), cos_tab.shape[0], TTT_BF16,
                               _stream_ptr(stream))
+    if rc != TTT_OK:
+        raise TttAttnError(rc, ttt_attn_last_error())
+
+
+def ttt_o_proj_fwd(o, w, out, stream=None):
+    """o [T, hq, d] (or [T, in]) and w [out_features, in] bf16, rows may be strided; writes out [T, out_features]."""
+    import torch
+    lib = load_library()
+    o2 = o.reshape(o.shape[0], -1) if o.dim() == 3 else o
+    T, fin = o2.shape
+    assert o2.dtype == w.dtype == out.dtype == torch.bfloat16 and o2.stride(1) == 1 and w.stride(1) == 1
+    assert w.shape[1] == fin and out.shape == (T, w.shape[0]) and out.is_contiguous()
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    rc = lib.ttt_o_proj_fwd(p(o2), p(w), p(out), T, fin, w.shape[0], o2.stride(0) if T > 1 else max(o2.stride(0), fin),
+                            w.stride(0), TTT_BF16, _stream_ptr(stream))
     if rc != TTT_OK:
         raise TttAttnError(rc, ttt_attn_last_error())

@@ -453,8 +453,28 @@ int ttt_qkv_rope_fwd(const void* x, const void* w, const float* cos_tab, const f
     for (const void* ptr : ptrs)
         if (reinterpret_cast<uintptr_t>(ptr) % 16) return fail(TTT_ERR_INVALID_ARG, "a tensor pointer is not 16-byte aligned");
     if (reinterpret_cast<uintptr_t>(pos) % 4) return fail(TTT_ERR_INVALID_ARG, "pos is not 4-byte aligned");
-    hipError_t e = ttt::launch_qkv_rope(x, w, cos_tab, sin_tab, pos, q, k, v, tokens, hidden_in, hq, hkv, x_row_stride,
+    hipError_t e = ttt::launch_qkv_rope(x, w, cos_tab, sin_tab, pos, q, k, v, tokens, hidden_in, hq, hkv, hkv, x_row_stride,
                                         w_row_stride, n_pos, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(TTT_ERR_HIP, "projection kernel launch: %s", hipGetErrorString(e));
+    return TTT_OK;
+}
+
+int ttt_o_proj_fwd(const void* o, const void* w, void* out, int64_t tokens, int32_t in_features, int32_t out_features,
+                   int64_t o_row_stride, int64_t w_row_stride, int32_t dtype, void* hip_stream) {
+    if (dtype != TTT_BF16) return fail(TTT_ERR_UNSUPPORTED, "dtype %d: the projection kernel is built for TTT_BF16", dtype);
+    if (tokens < 0 || tokens > 0x7fffffffLL) return fail(TTT_ERR_INVALID_ARG, "tokens=%lld out of range", (long long)tokens);
+    if (in_features < 64 || in_features % 64) return fail(TTT_ERR_INVALID_ARG, "in_features=%d must be a positive multiple of 64", in_features);
+    if (out_features < 128 || out_features % 128 || out_features > 128 * 8192)
+        return fail(TTT_ERR_INVALID_ARG, "out_features=%d must be a multiple of 128 in [128, 1048576]", out_features);
+    if (o_row_stride < in_features || w_row_stride < in_features || o_row_stride % 8 || w_row_stride % 8)
+        return fail(TTT_ERR_INVALID_ARG, "row strides (%lld, %lld) must be multiples of 8 and >= in_features=%d",
+                    (long long)o_row_stride, (long long)w_row_stride, in_features);
+    if (tokens == 0) return TTT_OK;
+    if (!o || !w || !out) return fail(TTT_ERR_INVALID_ARG, "a pointer is NULL");
+    if (reinterpret_cast<uintptr_t>(o) % 16 || reinterpret_cast<uintptr_t>(w) % 16 || reinterpret_cast<uintptr_t>(out) % 16)
+        return fail(TTT_ERR_INVALID_ARG, "a tensor pointer is not 16-byte aligned");
+    hipError_t e = ttt::launch_qkv_rope(o, w, nullptr, nullptr, nullptr, nullptr, nullptr, out, tokens, in_features, 0, 0,
+                                        out_features / 128, o_row_stride, w_row_stride, 1, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(TTT_ERR_HIP, "projection kernel launch: %s", hipGetErrorString(e));
     return TTT_OK;
 }

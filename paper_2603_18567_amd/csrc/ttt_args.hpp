@@ -71,8 +71,8 @@ hipError_t launch_loss_bwd(int dtype, void* logits, const void* target, const fl
                            int64_t logits_row_stride, int64_t target_row_stride, hipStream_t stream);
 
 hipError_t launch_qkv_rope(const void* x, const void* w, const float* cos_tab, const float* sin_tab, const int* pos, void* q,
-                           void* k, void* v, int64_t tokens, int hidden_in, int hq, int hkv, int64_t x_st, int64_t w_st,
-                           int n_pos, hipStream_t stream);
+                           void* k, void* v, int64_t tokens, int hidden_in, int n_q, int n_k, int n_v, int64_t x_st,
+                           int64_t w_st, int n_pos, hipStream_t stream);
 
 // Diagnostics (off by default): brackets one kernel launch with HIP events on its stream so that
 // a caller can read per-kernel durations afterwards (ttt_attn_profile_totals).

@@ -5,6 +5,8 @@
 //   y[t, f] = sum_c x[t, c] w[f, c]            bf16 operands, fp32 accumulation on the matrix cores
 //   Q, K heads: (y[i], y[i + d/2]) turned by the angle whose cos / sin the table holds at pos[t]
 //   V heads:    y as it is
+// With no rotated heads at all the same kernel is the plain projection y = x w^T (the output
+// projection that reads O_j).
 //
 // One workgroup = 256 tokens x 2 heads (256 features), eight waves: wave (wm, wn) owns 64 tokens x
 // the 128 features of head wn, i.e. 2 x 4 accumulator blocks of 32 x 32 (a 128-token variant, one
@@ -31,7 +33,8 @@ struct QkvArgs {
     void* q;
     void* k;
     void* v;
-    int T, Hin, hq, hkv, n_pos;
+    int T, Hin, n_pos;
+    int n_q, n_k, n_v;    // heads written to q (rotated), k (rotated), v (as they are); weight rows in this order
     int64_t x_st, w_st;   // row strides in elements
     int m_tiles, n_tiles, per_xcd;
 };
@@ -64,7 +67,7 @@ __global__ __launch_bounds__(512) void ttt_qkv_rope_kernel(const QkvArgs a) {
     if (tm >= a.m_tiles || tn >= a.n_tiles) return;
     const int m0 = tm * MT;
     const int n0 = tn * NT;
-    const int n_feat = (a.hq + 2 * a.hkv) * D;
+    const int n_feat = (a.n_q + a.n_k + a.n_v) * D;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave & 3, wn = wave >> 2;
@@ -145,19 +148,19 @@ __global__ __launch_bounds__(512) void ttt_qkv_rope_kernel(const QkvArgs a) {
     // ---- epilogue: rotate, convert, store.  Lane (n, hh) holds, of accumulator block (mb, nb), the
     // features 32 nb + 8 k4 + 4 hh + 0..3 (k4 = 0..3) of token m0 + 64 wm + 32 mb + n.
     const int head = n0 / D + wn;
-    if (head >= a.hq + 2 * a.hkv) return;
-    const bool rotate = head < a.hq + a.hkv;
+    if (head >= a.n_q + a.n_k + a.n_v) return;
+    const bool rotate = head < a.n_q + a.n_k;
     T* out;
     int64_t out_st;
-    if (head < a.hq) {
+    if (head < a.n_q) {
         out = static_cast<T*>(a.q) + (int64_t)head * D;
-        out_st = (int64_t)a.hq * D;
-    } else if (head < a.hq + a.hkv) {
-        out = static_cast<T*>(a.k) + (int64_t)(head - a.hq) * D;
-        out_st = (int64_t)a.hkv * D;
+        out_st = (int64_t)a.n_q * D;
+    } else if (head < a.n_q + a.n_k) {
+        out = static_cast<T*>(a.k) + (int64_t)(head - a.n_q) * D;
+        out_st = (int64_t)a.n_k * D;
     } else {
-        out = static_cast<T*>(a.v) + (int64_t)(head - a.hq - a.hkv) * D;
-        out_st = (int64_t)a.hkv * D;
+        out = static_cast<T*>(a.v) + (int64_t)(head - a.n_q - a.n_k) * D;
+        out_st = (int64_t)a.n_v * D;
     }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
@@ -222,9 +225,11 @@ static hipError_t launch_qkv_rope_t(QkvArgs& a, hipStream_t stream) {
     return hipGetLastError();
 }
 
+// n_q + n_k heads are rotated and go to q and k, n_v heads go to v as they are.  With n_q = n_k = 0 the
+// call is a plain projection y = x w^T into v ([tokens, n_v * 128]).
 hipError_t launch_qkv_rope(const void* x, const void* w, const float* cos_tab, const float* sin_tab, const int* pos, void* q,
-                           void* k, void* v, int64_t tokens, int hidden_in, int hq, int hkv, int64_t x_st, int64_t w_st,
-                           int n_pos, hipStream_t stream) {
+                           void* k, void* v, int64_t tokens, int hidden_in, int n_q, int n_k, int n_v, int64_t x_st,
+                           int64_t w_st, int n_pos, hipStream_t stream) {
     // 64 rows of x or w are addressed with 32-bit byte offsets
     if (x_st * 64 * 2 >= (int64_t)1 << 32 || w_st * 64 * 2 >= (int64_t)1 << 32) return hipErrorInvalidValue;
     QkvArgs a;
@@ -238,12 +243,13 @@ hipError_t launch_qkv_rope(const void* x, const void* w, const float* cos_tab, c
     a.v = v;
     a.T = (int)tokens;
     a.Hin = hidden_in;
-    a.hq = hq;
-    a.hkv = hkv;
+    a.n_q = n_q;
+    a.n_k = n_k;
+    a.n_v = n_v;
     a.n_pos = n_pos;
     a.x_st = x_st;
     a.w_st = w_st;
-    a.n_tiles = ((hq + 2 * hkv) * 128 + 255) / 256;
+    a.n_tiles = ((n_q + n_k + n_v) * 128 + 255) / 256;
     // Token tile of 256 or 128 rows: one workgroup per compute unit at a time, so the call takes
     // rounds x tile time; the small tile costs a little more than half of the large one.
     static int n_cu = 0;

@@ -25,7 +25,7 @@ def declared_functions():
     for fn in sorted(os.listdir(inc)):
         if fn.endswith(".h"):
             text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, fn)).read(), flags=re.S)
-            names |= set(re.findall(r"\b(ttt_(?:attn|loss|qkv)_\w+)\s*\(", text))
+            names |= set(re.findall(r"\b(ttt_(?:attn|loss|qkv|o)_\w+)\s*\(", text))
     return sorted(names)
 
 

@@ -126,3 +126,42 @@ def test_draft_layer_shape_sampled_tokens():
     check(k[rows], rk, "K")
     check(v[rows], rv, "V")
     assert np.isfinite(q).all() and np.isfinite(k).all() and np.isfinite(v).all()
+
+
+O_CASES = [
+    # name, T, hq, out_features, o_pad, w_pad
+    ("o_small_ragged", 300, 2, 384, 0, 0),          # 3 half-tiles of features: the last feature tile holds one
+    ("o_strided", 520, 4, 256, 128, 8),
+    ("o_draft_layer_rows", 4096, 32, 4096, 0, 0),   # the draft layer's shape (sampled tokens below)
+]
+
+
+@pytest.mark.parametrize("name,T,hq,nout,o_pad,w_pad", O_CASES, ids=[c[0] for c in O_CASES])
+def test_output_projection_matches_oracle(name, T, hq, nout, o_pad, w_pad):
+    from oracle.qkv_oracle import o_proj
+    from paper_2603_18567_amd import binding
+    d = 128
+    fin = hq * d
+    print(f"case {name} T={T} in={fin} out={nout}", flush=True)
+    gen = torch.Generator().manual_seed(500 + T)
+    o = torch.randn(T, fin + o_pad, generator=gen).to(torch.bfloat16)
+    w = (torch.randn(nout, fin + w_pad, generator=gen) / math.sqrt(fin)).to(torch.bfloat16)
+    dev = torch.device("cuda:0")
+    out = torch.full((T, nout), float("nan"), dtype=torch.bfloat16, device=dev)
+    binding.ttt_o_proj_fwd(o.to(dev)[:, :fin], w.to(dev)[:, :fin], out)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    rows = np.arange(T) if T <= 1024 else np.concatenate([[0, 255, 256, T - 1], np.random.default_rng(4).choice(T, 60, replace=False)])
+    ref = o_proj(o[rows, :fin].float().numpy(), w[:, :fin].float().numpy())
+    check(got[rows], ref, "out")
+    assert np.isfinite(got).all()
+
+
+def test_output_projection_argument_errors():
+    from paper_2603_18567_amd import binding
+    dev = torch.device("cuda:0")
+    bf = dict(dtype=torch.bfloat16, device=dev)
+    with pytest.raises(binding.TttAttnError):      # out_features not a multiple of 128
+        binding.ttt_o_proj_fwd(torch.zeros(8, 128, **bf), torch.zeros(100, 128, **bf), torch.zeros(8, 100, **bf))
+    with pytest.raises(binding.TttAttnError):      # in_features not a multiple of 64
+        binding.ttt_o_proj_fwd(torch.zeros(8, 96, **bf), torch.zeros(128, 96, **bf), torch.zeros(8, 128, **bf))
