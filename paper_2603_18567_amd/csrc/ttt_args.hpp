@@ -32,6 +32,7 @@ struct FwdArgs {
     const int* tok_start;   // [T] first token of each token's document
     int n_tiles;            // query tiles over the packed token axis
     int pack_log2;          // log2 of the query heads (of one kv group) that share a workgroup
+    int diag_lds;           // 1: the rows of the diagonal keys are staged in LDS (64-row workgroups)
     HeadMap map;
 };
 

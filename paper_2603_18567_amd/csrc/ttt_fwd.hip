@@ -30,6 +30,8 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
     constexpr int NT = NW * 64;
     constexpr int TILE_BYTES = KT * D * E::kBytes;
     constexpr float kLazy = 8.f;          // log2 of the largest p tolerated before the reference max moves
+    constexpr bool kDiagLds = sizeof(T) == 2 && KT == 64;   // diagonal rows may be staged in LDS (64-row tiles)
+    constexpr int kDiagSlots = 3;         // blocks whose rows are staged at once
 
     extern __shared__ __align__(16) char smem[];
     // LDS: K stage 0, K stage 1, V stage 0, V stage 1
@@ -214,10 +216,77 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
 
     // Diagonal keys of blocks 1..j (suffix part of the mask): one key per block and row, taken first
     // so that their global-memory latency overlaps the first tile copy.  Row-wise dot products on
-    // the vector ALU; the fragments of block lb+1 are requested before block lb is consumed.
-    if (active && j >= 1) {
-        frag dk[QB][DC], dv[QB][DC];
-        auto request = [&](int lb) {
+    // the vector ALU.
+    auto diag_key = [&](const frag (&dk)[QB][DC], const frag (&dv)[QB][DC]) {
+        float s[QB];
+        float vv[QB][DB][16];   // the key's value row in accumulator order
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            s[qb] = 0.f;
+#pragma unroll
+            for (int t = 0; t < DC; ++t) s[qb] = dot8(qf[qb][t], dk[qb][t], s[qb]);
+            frags_to_acc_order<T, DC>(dv[qb], vv[qb]);
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float sc = half_sum(s[qb]);
+            const bool grow = (sc - m[qb]) * c > kLazy;   // always for the first key (m = -inf)
+            if (__any(grow)) {
+                const float m_new = grow ? sc : m[qb];
+                const float alpha = grow ? fast_exp2((m[qb] - m_new) * c) : 1.f;
+                m[qb] = m_new;
+                l[qb] *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
+            }
+            const float p = fast_exp2((sc - m[qb]) * c);
+            l[qb] += 0.5f * p;   // the two lane halves are added at the end
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[qb][db][i] = fmaf(p, vv[qb][db][i], oacc[qb][db][i]);
+        }
+    };
+    if (a.diag_lds) {
+        // Workgroups of 64 rows (packed heads: all waves of a row block want the same K_l / V_l rows):
+        // the rows of up to kDiagSlots blocks are copied into LDS at once, behind the tile stages, so
+        // their latency is paid once per group of blocks, not once per block, and once per kv group,
+        // not once per head.  j is the same for the whole workgroup: the barriers are uniform.
+        if constexpr (kDiagLds) {
+            char* dbase = smem + 4 * TILE_BYTES;
+            for (int base = 1; base <= j; base += kDiagSlots) {
+                const int nb = min(kDiagSlots, j - base + 1);
+                if (base > 1) __syncthreads();   // the slots are free again
+                for (int i = 0; i < nb; ++i) {
+                    const T* Kl = static_cast<const T*>(a.k[base + i]) + (int64_t)g * geo.kv_sh;
+                    const T* Vl = static_cast<const T*>(a.v[base + i]) + (int64_t)g * geo.kv_sh;
+                    tile_load_async<T, D, 64, NT>(dbase + (2 * i) * TILE_BYTES, Kl, geo.kv_st, q_tile0, Tn - 1, tid);
+                    tile_load_async<T, D, 64, NT>(dbase + (2 * i + 1) * TILE_BYTES, Vl, geo.kv_st, q_tile0, Tn - 1, tid);
+                }
+                wait_async_copies();
+                __syncthreads();
+                if (active) {
+                    const int rb = (wq0 - q_tile0) / 32;   // this wave's first row block inside the workgroup's rows
+                    for (int i = 0; i < nb; ++i) {
+                        frag dk[QB][DC], dv[QB][DC];
+#pragma unroll
+                        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                            for (int t = 0; t < DC; ++t) {
+                                dk[qb][t] = lf.rowwise(dbase + (2 * i) * TILE_BYTES, rb + qb, t);
+                                dv[qb][t] = lf.rowwise(dbase + (2 * i + 1) * TILE_BYTES, rb + qb, t);
+                            }
+                        diag_key(dk, dv);
+                    }
+                }
+            }
+        }
+    } else if (active && j >= 1) {
+        // the fragments of block lb + 1 are requested from global memory before block lb is consumed
+        frag dk[QB][DC], dv[QB][DC], nk[QB][DC], nv[QB][DC];
+        auto request = [&](int lb, frag (&rk)[QB][DC], frag (&rv)[QB][DC]) {
             const T* Kl = static_cast<const T*>(a.k[lb]) + (int64_t)g * geo.kv_sh;
             const T* Vl = static_cast<const T*>(a.v[lb]) + (int64_t)g * geo.kv_sh;
 #pragma unroll
@@ -226,44 +295,22 @@ __global__ __launch_bounds__(NW * 64, MINB) void ttt_fwd_kernel(const FwdArgs a)
                 const T* vrow = Vl + (int64_t)qc[qb] * geo.kv_st;
 #pragma unroll
                 for (int t = 0; t < DC; ++t) {
-                    dk[qb][t] = gload_frag<T>(krow + t * 16 + hh * 8);
-                    dv[qb][t] = gload_frag<T>(vrow + t * 16 + hh * 8);
+                    rk[qb][t] = gload_frag<T>(krow + t * 16 + hh * 8);
+                    rv[qb][t] = gload_frag<T>(vrow + t * 16 + hh * 8);
                 }
             }
         };
-        request(1);
+        request(1, dk, dv);
         for (int lb = 1; lb <= j; ++lb) {
-            float s[QB];
-            float vv[QB][DB][16];   // the key's value row in accumulator order
+            if (lb < j) request(lb + 1, nk, nv);
+            diag_key(dk, dv);
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                s[qb] = 0.f;
+            for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-                for (int t = 0; t < DC; ++t) s[qb] = dot8(qf[qb][t], dk[qb][t], s[qb]);
-                frags_to_acc_order<T, DC>(dv[qb], vv[qb]);
-            }
-            if (lb < j) request(lb + 1);
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                const float sc = half_sum(s[qb]);
-                const bool grow = (sc - m[qb]) * c > kLazy;   // always for the first key (m = -inf)
-                if (__any(grow)) {
-                    const float m_new = grow ? sc : m[qb];
-                    const float alpha = grow ? fast_exp2((m[qb] - m_new) * c) : 1.f;
-                    m[qb] = m_new;
-                    l[qb] *= alpha;
-#pragma unroll
-                    for (int db = 0; db < DB; ++db)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) oacc[qb][db][i] *= alpha;
+                for (int t = 0; t < DC; ++t) {
+                    dk[qb][t] = nk[qb][t];
+                    dv[qb][t] = nv[qb][t];
                 }
-                const float p = fast_exp2((sc - m[qb]) * c);
-                l[qb] += 0.5f * p;   // the two lane halves are added at the end
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) oacc[qb][db][i] = fmaf(p, vv[qb][db][i], oacc[qb][db][i]);
-            }
         }
     }
 
@@ -334,6 +381,7 @@ hipError_t launch_tok_bounds(const int* cu_dev, int base, int n_docs, int T, int
 template <typename T, int D, int QB, int NW, int MINB> struct FwdCfg {
     static constexpr int kQT = NW * QB * 32;
     static constexpr int kLds = 4 * 64 * D * (int)sizeof(T);   // two stages of K and V tiles
+    static constexpr int kDiagLds = 3 * 2 * 64 * D * (int)sizeof(T);   // three blocks of 64 diagonal K and V rows
 };
 
 template <typename T, int D, int QB, int NW, int MINB> static hipError_t launch_fwd_t(FwdArgs& a, hipStream_t stream) {
@@ -341,7 +389,8 @@ template <typename T, int D, int QB, int NW, int MINB> static hipError_t launch_
     auto kern = ttt_fwd_kernel<T, D, QB, NW, MINB>;
     static bool attr_done = false;   // benign race: the attribute is idempotent
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           C::kLds + (sizeof(T) == 2 ? C::kDiagLds : 0));
         if (e != hipSuccess) return e;
         attr_done = true;
     }
@@ -352,6 +401,8 @@ template <typename T, int D, int QB, int NW, int MINB> static hipError_t launch_
     while ((2 << a.pack_log2) <= 4 && geo.G % (2 << a.pack_log2) == 0 && NW % (2 << a.pack_log2) == 0) ++a.pack_log2;
     const int qt_rows = C::kQT >> a.pack_log2;
     a.n_tiles = (geo.T + qt_rows - 1) / qt_rows;
+    a.diag_lds = sizeof(T) == 2 && qt_rows == 64;   // the diagonal rows of a 64-row workgroup go through LDS
+    const int lds_bytes = C::kLds + (a.diag_lds ? C::kDiagLds : 0);
     a.map.hkv = geo.hkv;
     a.map.rest_count = a.n_tiles * geo.n_steps * (geo.G >> a.pack_log2);
     int64_t grid;
@@ -371,7 +422,7 @@ template <typename T, int D, int QB, int NW, int MINB> static hipError_t launch_
     // the 16-bit kernels address the pieces of up to 64 rows of K or V with 32-bit byte offsets
     if (sizeof(T) == 2 && geo.kv_st * 64 * (int64_t)sizeof(T) >= (int64_t)1 << 32) return hipErrorInvalidValue;
     ProfileScope prof("ttt_fwd_kernel", stream);
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), C::kLds, stream, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), lds_bytes, stream, a);
     return hipGetLastError();
 }
 
