@@ -23,7 +23,7 @@ PEAK_F32_TFLOPS = 157.3       # MI355X fp32 MFMA/vector
 # HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
 # command (profiles/headline_4k_hbm_traffic.txt: fetch scaled by the copy calibration, plus write);
 # a counter cannot be read from inside this process, so the recorded figure is reported.
-RECORDED_TRAFFIC = {("headline_4k", "ttt_bwd_dkv_kernel"): 887.4e6 + 302.0e6}
+RECORDED_TRAFFIC = {("headline_4k", "ttt_bwd_dkv_kernel"): 912.6e6 + 302.0e6}
 
 
 def parse():
