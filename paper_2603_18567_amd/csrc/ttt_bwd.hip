@@ -708,10 +708,17 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
     __syncthreads();   // everybody is done with the tile stages: they become the store patches
     if (!active) return;
 
-    // diagonal keys of blocks 1..j; the rows of block lb+1 are requested before block lb is consumed
+    // Diagonal keys of blocks 1..j.  The workgroup's LDS is free now and every wave has 16 KB of it to
+    // itself (its store patch lies inside): the K_l / V_l rows of the wave's 32 tokens are copied there
+    // by LDS-DMA as whole 256-byte rows (fragment loads straight from global memory would touch 32 rows
+    // with 32 bytes each per instruction) and read back as fragments; the copy of block lb + 1 is
+    // requested as soon as the fragments of block lb are in registers.
+    constexpr int WAVE_LDS = 2 * 32 * D * E::kBytes;
+    static_assert(NW * WAVE_LDS <= 2 * STAGE_BYTES, "one region per wave");
+    char* wbuf = smem + wave * WAVE_LDS;
     if (j >= 1) {
         frag dk[DC], dv[DC];
-        auto request = [&](int lb) {
+        auto request = [&](int lb) {   // straight from global memory (rows past the end clamped)
             const T* krow = static_cast<const T*>(a.k[lb]) + (int64_t)g * geo.kv_sh + (int64_t)qc * geo.kv_st;
             const T* vrow = static_cast<const T*>(a.v[lb]) + (int64_t)g * geo.kv_sh + (int64_t)qc * geo.kv_st;
 #pragma unroll
@@ -720,21 +727,15 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
                 dv[t] = gload_frag<T>(vrow + t * 16 + hh * 8);
             }
         };
-        // (with two waves per SIMD the other wave covers the load latency, and requesting one block
-        // ahead would not fit the registers)
-        constexpr bool kAhead = NW != 8;
-        if (kAhead) request(1);
-        for (int lb = 1; lb <= j; ++lb) {
+        auto apply = [&]() {
             float s = 0.f, dp = 0.f;
             uint32_t kk[DC][4];   // the key row in accumulator order, still packed
-            if (!kAhead) request(lb);
 #pragma unroll
             for (int t = 0; t < DC; ++t) {
                 s = dot8(qf[t], dk[t], s);
                 dp = dot8(gof[t], dv[t], dp);
             }
             frags_to_acc_order_packed<T, DC>(dk, kk);
-            if (kAhead && lb < j) request(lb + 1);
             s = half_sum(s);
             dp = half_sum(dp);
             const float p = fast_exp2(fmaf(s, c, -lse2));
@@ -743,11 +744,53 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) dqacc[db][i] = fmaf(ds, acc_order_elem<DC>(kk, db, i), dqacc[db][i]);
+        };
+        if (wq0 + 32 <= Tn) {
+            constexpr int NCP = 32 * TL::kPieces / 64;   // copy instructions per 32-row matrix
+            uint32_t doff[NCP];                          // this lane's piece: bytes from the first row
+#pragma unroll
+            for (int it = 0; it < NCP; ++it) {
+                const int pidx = it * 64 + lane;
+                const int r = pidx / TL::kPieces, pos = pidx % TL::kPieces;
+                doff[it] = (uint32_t)((r * geo.kv_st + (pos ^ TL::swz(r)) * TL::kElemsPerPiece) * (int64_t)sizeof(T));
+            }
+            const uint32_t wl = __builtin_amdgcn_readfirstlane(lds0 + wave * WAVE_LDS);
+            const int wq0u = __builtin_amdgcn_readfirstlane(wq0);   // wave-uniform copies of per-wave values
+            auto copy = [&](int lb) {
+                const T* kb = static_cast<const T*>(a.k[lb]) + (int64_t)g * geo.kv_sh + (int64_t)wq0u * geo.kv_st;
+                const T* vb = static_cast<const T*>(a.v[lb]) + (int64_t)g * geo.kv_sh + (int64_t)wq0u * geo.kv_st;
+#pragma unroll
+                for (int it = 0; it < NCP; ++it) {
+                    async_copy16(kb, doff[it], wl + it * 1024);
+                    async_copy16(vb, doff[it], wl + WAVE_LDS / 2 + it * 1024);
+                }
+            };
+            LaneFrags<T, D> lf;
+            lf.init(lane);
+            copy(1);
+            for (int lb = 1; lb <= j; ++lb) {
+                wait_async_copies();
+#pragma unroll
+                for (int t = 0; t < DC; ++t) {
+                    dk[t] = lf.rowwise(wbuf, 0, t);
+                    dv[t] = lf.rowwise(wbuf + WAVE_LDS / 2, 0, t);
+                }
+                if (lb < j) {
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the region is read out: refill it
+                    copy(lb + 1);
+                }
+                apply();
+            }
+        } else {
+            for (int lb = 1; lb <= j; ++lb) {
+                request(lb);
+                apply();
+            }
         }
     }
 
     // scaled rows go through a wave-private LDS patch so that global stores are whole 16-byte pieces
-    char* patch = smem + wave * (32 * D * E::kBytes);
+    char* patch = wbuf;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
