@@ -748,9 +748,11 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
         if (wq0 + 32 <= Tn) {
             constexpr int NCP = 32 * TL::kPieces / 64;   // copy instructions per 32-row matrix
             uint32_t doff[NCP];                          // this lane's piece: bytes from the first row
+            int lane_here = lane;
+            asm volatile("" : "+v"(lane_here));          // computed here, not carried through the main loop
 #pragma unroll
             for (int it = 0; it < NCP; ++it) {
-                const int pidx = it * 64 + lane;
+                const int pidx = it * 64 + lane_here;
                 const int r = pidx / TL::kPieces, pos = pidx % TL::kPieces;
                 doff[it] = (uint32_t)((r * geo.kv_st + (pos ^ TL::swz(r)) * TL::kElemsPerPiece) * (int64_t)sizeof(T));
             }
@@ -766,7 +768,7 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
                 }
             };
             LaneFrags<T, D> lf;
-            lf.init(lane);
+            lf.init(lane_here);
             copy(1);
             for (int lb = 1; lb <= j; ++lb) {
                 wait_async_copies();
