@@ -42,7 +42,17 @@ class Case:
         return (stack_np(self.inp.q), stack_np(self.inp.k), stack_np(self.inp.v), stack_np(self.inp.d_o))
 
 
-def check(name, got, ref, dtype, lse=False):
+# Worst per-row ratio error / (2e-2 * max|row| + floor) seen by check(..., rows=True), per tensor kind
+# ("O", "dQ"): printed by the full-size tests so that the margin of the per-row bound is on record.
+WORST_ROW_RATIO = {}
+
+
+def check(name, got, ref, dtype, lse=False, rows=False):
+    """Per-tensor bound (the stated tolerance).  With rows=True and bf16 inputs, additionally every
+    row (last axis = head_dim) must satisfy max|err_row| <= 2e-2 * max|ref_row| + floor: the tensor
+    maximum is set by the few rows with a short prefix (|O| ~ |V|), and a row averaged over thousands
+    of keys is 30-100 times smaller, so the per-tensor bound alone would pass a late row that is
+    wrong by half of its own magnitude."""
     tol = TOL[dtype]
     got = np.asarray(got, dtype=np.float64)
     assert np.isfinite(got).all(), f"{name}: non-finite values on the GPU side"
@@ -54,6 +64,15 @@ def check(name, got, ref, dtype, lse=False):
     else:
         bound = max(tol["val"] * float(np.abs(ref).max()), tol["floor"])
     assert err <= bound, f"{name}: max abs err {err:.3e} > bound {bound:.3e}"
+    if rows and not lse and tol["kind"] == "rel" and got.size:
+        row_err = np.abs(got - ref).max(axis=-1)
+        row_bound = tol["val"] * np.abs(ref).max(axis=-1) + tol["floor"]
+        ratio = row_err / row_bound
+        worst = int(np.argmax(ratio))
+        kind = name.split("[")[0].split(" ")[0]
+        WORST_ROW_RATIO[kind] = max(WORST_ROW_RATIO.get(kind, 0.0), float(ratio.flat[worst]))
+        assert ratio.flat[worst] <= 1.0, (f"{name}: row {np.unravel_index(worst, ratio.shape)} has max abs err "
+                                          f"{row_err.flat[worst]:.3e} > per-row bound {row_bound.flat[worst]:.3e}")
     return err, bound
 
 
@@ -67,10 +86,10 @@ def compare_full(case, step_begin=0, step_end=None, report=None):
     torch.cuda.synchronize()
     errs = {}
     for n, j in enumerate(range(step_begin, step_end)):
-        errs[f"O{j}"] = check(f"O[{j}]", to_np32(run.o[j]), Oo[n], wl.dtype)
+        errs[f"O{j}"] = check(f"O[{j}]", to_np32(run.o[j]), Oo[n], wl.dtype, rows=True)
         errs[f"LSE{j}"] = check(f"LSE[{j}]", to_np32(run.lse[j]), LSEo[n], wl.dtype, lse=True)
         if run.dq is not None:
-            errs[f"dQ{j}"] = check(f"dQ[{j}]", to_np32(run.dq[j]), dQo[n], wl.dtype)
+            errs[f"dQ{j}"] = check(f"dQ[{j}]", to_np32(run.dq[j]), dQo[n], wl.dtype, rows=True)
     if run.dk is not None:
         for l in range(step_end):
             errs[f"dK{l}"] = check(f"dK[{l}]", to_np32(run.dk[l]), dKo[l], wl.dtype)
