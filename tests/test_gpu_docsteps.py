@@ -7,7 +7,7 @@ import torch
 
 import oracle as O
 from paper_2603_18567_amd.workloads import custom_workload
-from ttt_testlib import Case, check, to_np32
+from ttt_testlib import Case, check, dq_row_slack, to_np32
 
 pytestmark = pytest.mark.gpu
 
@@ -122,7 +122,8 @@ def test_docsteps_on_the_packed_varlen_workload():
     print(f"  oracle on {len(rows)} rows done", flush=True)
     check("O rows", np.stack([to_np32(run.o[j][i]) for j, i in zip(rs, rt)]), ref.O, wl.dtype, rows=True)
     check("LSE rows", np.stack([to_np32(run.lse[j][:, i]) for j, i in zip(rs, rt)]), ref.LSE, wl.dtype, lse=True)
-    check("dQ rows", np.stack([to_np32(run.dq[j][i]) for j, i in zip(rs, rt)]), ref.dQ, wl.dtype, rows=True)
+    slack = dq_row_slack(dO_rows, ref.O, O.oracle_run(Q, K, K, cu, wl.scale, rs, rt).O, wl.scale)
+    check("dQ rows", np.stack([to_np32(run.dq[j][i]) for j, i in zip(rs, rt)]), ref.dQ, wl.dtype, rows=True, row_slack=slack)
     dev = run.o[0].device
     for j in range(wl.k):
         off = ~act[j].to(dev)

@@ -8,7 +8,7 @@ import torch
 
 import oracle as O
 from paper_2603_18567_amd.workloads import WORKLOADS, custom_workload
-from ttt_testlib import WORST_ROW_RATIO, Case, check, compare_full, to_np32
+from ttt_testlib import WORST_ROW_RATIO, Case, check, compare_full, dq_row_slack, to_np32
 
 pytestmark = pytest.mark.gpu
 
@@ -234,6 +234,7 @@ def test_full_size_workload_sampled_rows_and_invariants(name):
     Q, K, V, _ = case.oracle_inputs()
     dO_rows = np.stack([case.inp.d_o[j][i].to(torch.float32).numpy() for j, i in zip(rs, rt)])
     ref = O.oracle_run(Q, K, V, wl.cu_seqlens, wl.scale, rs, rt, dO_rows)
+    slack = dq_row_slack(dO_rows, ref.O, O.oracle_run(Q, K, K, wl.cu_seqlens, wl.scale, rs, rt).O, wl.scale)
     print(f"  oracle on {len(rs)} rows done", flush=True)
     got_O = np.stack([to_np32(run.o[j][i]) for j, i in zip(rs, rt)])
     got_L = np.stack([to_np32(run.lse[j][:, i]) for j, i in zip(rs, rt)])
@@ -241,7 +242,7 @@ def test_full_size_workload_sampled_rows_and_invariants(name):
     WORST_ROW_RATIO.clear()
     check("O rows", got_O, ref.O, wl.dtype, rows=True)
     check("LSE rows", got_L, ref.LSE, wl.dtype, lse=True)
-    check("dQ rows", got_dQ, ref.dQ, wl.dtype, rows=True)
+    check("dQ rows", got_dQ, ref.dQ, wl.dtype, rows=True, row_slack=slack)
     print(f"  worst per-row error / per-row bound: {WORST_ROW_RATIO}", flush=True)
     # second backward with a cotangent that is zero off the sampled rows: linear in dO, same kernel
     # work, and the oracle's sums over the listed rows are then the complete dK, dV
@@ -259,4 +260,4 @@ def test_full_size_workload_sampled_rows_and_invariants(name):
         off = run.dq[j][~keep[j].to(run.dq[j].device)]
         assert (off == 0).all(), "dQ must vanish where the cotangent row is zero"
     got_dQ2 = np.stack([to_np32(run.dq[j][i]) for j, i in zip(rs, rt)])
-    check("dQ rows (row-sparse dO)", got_dQ2, ref.dQ, wl.dtype, rows=True)
+    check("dQ rows (row-sparse dO)", got_dQ2, ref.dQ, wl.dtype, rows=True, row_slack=slack)

@@ -47,9 +47,23 @@ class Case:
 WORST_ROW_RATIO = {}
 
 
-def check(name, got, ref, dtype, lse=False, rows=False):
+def dq_row_slack(dO_rows, O_rows, Kbar_rows, scale):
+    """What the rounding of the STORED O_j adds to a row of dQ_j, as a bound per (row, head).
+    The backward takes D = <dO, O> from the O the forward wrote (bf16: each element within 2^-8
+    relative of the exact one), the oracle from its own fp64 O; ds = p (dp - D) then moves by
+    -p * dD for every key of the row, i.e. dQ moves by -scale * dD * sum_m p_m K_m.  With
+    |dD| <= 2^-8 sum_c |dO_c O_c| (doubled here for the accumulated rounding of p in O) this is
+    2^-7 * scale * sum_c |dO_c O_c| * max_c |Kbar_c|, Kbar = sum_m p_m K_m -- the oracle's forward
+    with the keys in place of the values.  It matters for rows whose softmax is nearly one-hot
+    (dp - D cancels, dQ is tiny); for a row spread over many keys it is negligible."""
+    dD = 2.0 ** -7 * np.abs(np.asarray(dO_rows, np.float64) * O_rows).sum(-1)
+    return scale * dD * np.abs(Kbar_rows).max(-1)
+
+
+def check(name, got, ref, dtype, lse=False, rows=False, row_slack=None):
     """Per-tensor bound (the stated tolerance).  With rows=True and bf16 inputs, additionally every
-    row (last axis = head_dim) must satisfy max|err_row| <= 2e-2 * max|ref_row| + floor: the tensor
+    row (last axis = head_dim) must satisfy max|err_row| <= 2e-2 * max|ref_row| + floor
+    (+ row_slack, see dq_row_slack): the tensor
     maximum is set by the few rows with a short prefix (|O| ~ |V|), and a row averaged over thousands
     of keys is 30-100 times smaller, so the per-tensor bound alone would pass a late row that is
     wrong by half of its own magnitude."""
@@ -67,6 +81,8 @@ def check(name, got, ref, dtype, lse=False, rows=False):
     if rows and not lse and tol["kind"] == "rel" and got.size:
         row_err = np.abs(got - ref).max(axis=-1)
         row_bound = tol["val"] * np.abs(ref).max(axis=-1) + tol["floor"]
+        if row_slack is not None:
+            row_bound = row_bound + row_slack
         ratio = row_err / row_bound
         worst = int(np.argmax(ratio))
         kind = name.split("[")[0].split(" ")[0]
@@ -82,6 +98,10 @@ def compare_full(case, step_begin=0, step_end=None, report=None):
     Q, K, V, dO = case.oracle_inputs()
     step_end = wl.k if step_end is None else step_end
     Oo, LSEo, dQo, dKo, dVo = O.oracle_full(Q, K, V, wl.cu_seqlens, wl.scale, dO, step_begin, step_end)
+    slack = None
+    if wl.dtype == "bf16":
+        Kbar = O.oracle_full(Q, K, K, wl.cu_seqlens, wl.scale, None, step_begin, step_end)[0]
+        slack = dq_row_slack(dO[step_begin:step_end], Oo, Kbar, wl.scale)
     run = case.run
     torch.cuda.synchronize()
     errs = {}
@@ -89,7 +109,8 @@ def compare_full(case, step_begin=0, step_end=None, report=None):
         errs[f"O{j}"] = check(f"O[{j}]", to_np32(run.o[j]), Oo[n], wl.dtype, rows=True)
         errs[f"LSE{j}"] = check(f"LSE[{j}]", to_np32(run.lse[j]), LSEo[n], wl.dtype, lse=True)
         if run.dq is not None:
-            errs[f"dQ{j}"] = check(f"dQ[{j}]", to_np32(run.dq[j]), dQo[n], wl.dtype, rows=True)
+            errs[f"dQ{j}"] = check(f"dQ[{j}]", to_np32(run.dq[j]), dQo[n], wl.dtype, rows=True,
+                                   row_slack=None if slack is None else slack[n])
     if run.dk is not None:
         for l in range(step_end):
             errs[f"dK{l}"] = check(f"dK[{l}]", to_np32(run.dk[l]), dKo[l], wl.dtype)
