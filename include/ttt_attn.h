@@ -159,6 +159,24 @@ int ttt_attn_bwd_docsteps(const ttt_attn_params* params, const int32_t* doc_step
                           void* const* dq, void* const* dk, void* const* dv, void* workspace, size_t workspace_bytes,
                           void* hip_stream);
 
+/*
+ * ttt_attn_fwd for callers that cannot hand over (or allocate) a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid device allocation.  Same operation, arguments,
+ * layouts and errors as ttt_attn_fwd, minus the workspace: the per-token document bounds that the
+ * forward kernels read are kept in a device array built into the library (2 x TTT_STATIC_MAX_TOKENS
+ * int32 = 4 MiB on every GPU the library runs on, held until the process ends).  The call allocates
+ * no device memory and calls no allocating routine.  total_tokens > TTT_STATIC_MAX_TOKENS is
+ * rejected with TTT_ERR_WORKSPACE.  All calls on one GPU share that array (it is fully rewritten
+ * for the call's tokens before it is read, nothing needs clearing): calls that overlap in time on
+ * the same GPU -- different streams or threads -- race; calls on one stream are ordered and safe.
+ * The device that owns `hip_stream` must be the current device, as for every launch.
+ */
+#define TTT_STATIC_MAX_TOKENS 524288
+int ttt_attn_fwd_static(const ttt_attn_params* params,
+                        const void* const* q, const void* const* k, const void* const* v,
+                        const int32_t* cu_seqlens_dev, const int32_t* cu_seqlens_host,
+                        void* const* o, float* const* lse, void* hip_stream);
+
 /* Message of the calling thread's most recent failing call ("" if none).  Never NULL. */
 const char* ttt_attn_last_error(void);
 

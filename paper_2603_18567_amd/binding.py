@@ -19,7 +19,8 @@ TTT_MAX_STEPS = 32
 
 EXPORTS = ("ttt_attn_workspace_bytes", "ttt_attn_fwd", "ttt_attn_bwd", "ttt_attn_last_error",
            "ttt_attn_profile_enable", "ttt_attn_profile_totals", "ttt_attn_fwd_docsteps", "ttt_attn_bwd_docsteps",
-           "ttt_loss_bwd_inplace", "ttt_qkv_rope_fwd", "ttt_o_proj_fwd")
+           "ttt_loss_bwd_inplace", "ttt_qkv_rope_fwd", "ttt_o_proj_fwd", "ttt_attn_fwd_static")
+TTT_STATIC_MAX_TOKENS = 524288
 
 
 class TttAttnParams(ctypes.Structure):
@@ -58,6 +59,8 @@ def load_library():
         lib.ttt_attn_fwd.restype = ctypes.c_int
         lib.ttt_attn_fwd.argtypes = [ctypes.POINTER(TttAttnParams), pp, pp, pp, vp, vp, pp, pp,
                                      vp, ctypes.c_size_t, vp]
+        lib.ttt_attn_fwd_static.restype = ctypes.c_int
+        lib.ttt_attn_fwd_static.argtypes = [ctypes.POINTER(TttAttnParams), pp, pp, pp, vp, vp, pp, pp, vp]
         lib.ttt_attn_bwd.restype = ctypes.c_int
         lib.ttt_attn_bwd.argtypes = [ctypes.POINTER(TttAttnParams), pp, pp, pp, pp, pp, pp, vp, vp,
                                      pp, pp, pp, ctypes.c_int, vp, ctypes.c_size_t, vp]
@@ -151,6 +154,17 @@ def ttt_attn_fwd(params, q, k, v, cu_seqlens_dev, cu_seqlens_host, o, lse, works
                           _ptr_array(o, K), _ptr_array(lse, K),
                           ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                           _stream_ptr(stream))
+    if rc != TTT_OK:
+        raise TttAttnError(rc, ttt_attn_last_error())
+
+
+def ttt_attn_fwd_static(params, q, k, v, cu_seqlens_dev, cu_seqlens_host, o, lse, stream=None):
+    """ttt_attn_fwd without a workspace (the library's built-in scratch; at most TTT_STATIC_MAX_TOKENS tokens)."""
+    lib = load_library()
+    K = params.k
+    rc = lib.ttt_attn_fwd_static(ctypes.byref(params), _ptr_array(q, K), _ptr_array(k, K), _ptr_array(v, K),
+                                 ctypes.c_void_p(cu_seqlens_dev.data_ptr()), _cu_host_array(cu_seqlens_host),
+                                 _ptr_array(o, K), _ptr_array(lse, K), _stream_ptr(stream))
     if rc != TTT_OK:
         raise TttAttnError(rc, ttt_attn_last_error())
 

@@ -154,6 +154,42 @@ void profile_end(hipStream_t stream) {
 
 }  // namespace ttt
 
+// ---- forward without a workspace argument: the token-bounds scratch lives in a file-scope device
+// array.  Host code never uses the array's name as an address (on the host it is only a stand-in
+// for the symbol): the device address is asked for once per device and kept.
+static __device__ __align__(256) int32_t g_static_scratch[2 * TTT_STATIC_MAX_TOKENS];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+void* g_static_ptr[kMaxDevices] = {};
+
+// device address of g_static_scratch on the CURRENT device (nullptr + error message on failure)
+void* static_scratch_ptr() {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        fail(TTT_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+        return nullptr;
+    }
+    if (dev < 0 || dev >= kMaxDevices) {
+        fail(TTT_ERR_UNSUPPORTED, "device index %d outside 0..%d", dev, kMaxDevices - 1);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch));
+        if (e != hipSuccess || !ptr) {
+            fail(TTT_ERR_HIP, "hipGetSymbolAddress(static scratch) on device %d: %s", dev, hipGetErrorString(e));
+            return nullptr;
+        }
+        g_static_ptr[dev] = ptr;
+    }
+    return g_static_ptr[dev];
+}
+}  // namespace
+
 extern "C" {
 
 int ttt_attn_profile_enable(int on) {
@@ -264,15 +300,19 @@ static int make_slices(const ttt_attn_params* p, const int32_t* cu_host, const i
     return TTT_OK;
 }
 
-static int fwd_checked(const ttt_attn_params* p, const int32_t* doc_steps, const void* const* q, const void* const* k,
-                       const void* const* v, const int32_t* cu_dev, const int32_t* cu_host, void* const* o, float* const* lse,
-                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+// Everything the forward checks before it touches the workspace or launches anything.
+static int fwd_validate(const ttt_attn_params* p, const void* const* q, const void* const* k, const void* const* v,
+                        const int32_t* cu_dev, const int32_t* cu_host, void* const* o, float* const* lse, bool& nothing_to_do) {
+    nothing_to_do = false;
     int rc = check_params(p);
     if (rc != TTT_OK) return rc;
     if (!q || !k || !v || !o || !lse) return fail(TTT_ERR_INVALID_ARG, "a step-pointer array is NULL");
     rc = check_cu(p, cu_dev, cu_host);
     if (rc != TTT_OK) return rc;
-    if (p->total_tokens == 0 || p->step_begin == p->step_end) return TTT_OK;
+    if (p->total_tokens == 0 || p->step_begin == p->step_end) {
+        nothing_to_do = true;
+        return TTT_OK;
+    }
     for (int j = p->step_begin; j < p->step_end; ++j) {
         if ((rc = check_ptr(q[j], "q", j)) != TTT_OK) return rc;
         if ((rc = check_ptr(o[j], "o", j)) != TTT_OK) return rc;
@@ -282,6 +322,15 @@ static int fwd_checked(const ttt_attn_params* p, const int32_t* doc_steps, const
         if ((rc = check_ptr(k[l], "k", l)) != TTT_OK) return rc;
         if ((rc = check_ptr(v[l], "v", l)) != TTT_OK) return rc;
     }
+    return TTT_OK;
+}
+
+static int fwd_checked(const ttt_attn_params* p, const int32_t* doc_steps, const void* const* q, const void* const* k,
+                       const void* const* v, const int32_t* cu_dev, const int32_t* cu_host, void* const* o, float* const* lse,
+                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+    bool nothing = false;
+    int rc = fwd_validate(p, q, k, v, cu_dev, cu_host, o, lse, nothing);
+    if (rc != TTT_OK || nothing) return rc;
     const Layout L = make_layout(p, TTT_PASS_FWD);
     if ((rc = check_workspace(workspace, workspace_bytes, L.total)) != TTT_OK) return rc;
     std::vector<Slice> slices;
@@ -297,6 +346,24 @@ int ttt_attn_fwd(const ttt_attn_params* p, const void* const* q, const void* con
                  const int32_t* cu_dev, const int32_t* cu_host, void* const* o, float* const* lse, void* workspace,
                  size_t workspace_bytes, void* hip_stream) {
     return fwd_checked(p, nullptr, q, k, v, cu_dev, cu_host, o, lse, workspace, workspace_bytes, hip_stream);
+}
+
+int ttt_attn_fwd_static(const ttt_attn_params* p, const void* const* q, const void* const* k, const void* const* v,
+                        const int32_t* cu_dev, const int32_t* cu_host, void* const* o, float* const* lse, void* hip_stream) {
+    bool nothing = false;
+    int rc = fwd_validate(p, q, k, v, cu_dev, cu_host, o, lse, nothing);
+    if (rc != TTT_OK) return rc;
+    if (p->total_tokens > TTT_STATIC_MAX_TOKENS)
+        return fail(TTT_ERR_WORKSPACE, "total_tokens = %d exceeds TTT_STATIC_MAX_TOKENS = %d of the built-in scratch; use ttt_attn_fwd",
+                    p->total_tokens, TTT_STATIC_MAX_TOKENS);
+    if (nothing) return TTT_OK;
+    const Layout L = make_layout(p, TTT_PASS_FWD);
+    if (L.total > sizeof(int32_t) * 2 * (size_t)TTT_STATIC_MAX_TOKENS)
+        return fail(TTT_ERR_WORKSPACE, "built-in scratch too small for %d tokens", p->total_tokens);
+    void* scratch = static_scratch_ptr();
+    if (!scratch) return TTT_ERR_HIP;
+    const Slice whole{0, p->n_docs, 0, p->total_tokens, p->step_begin, p->step_end};
+    return fwd_slice(p, whole, q, k, v, cu_dev, cu_host, o, lse, static_cast<char*>(scratch), static_cast<hipStream_t>(hip_stream));
 }
 
 int ttt_attn_fwd_docsteps(const ttt_attn_params* p, const int32_t* doc_steps_host, const void* const* q, const void* const* k,
