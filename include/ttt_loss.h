@@ -1,14 +1,12 @@
 /*
  * ttt_loss.h -- C ABI of the in-place backward of the log-softmax loss on MI355X (gfx950).
  *
- * Operation (Sec. 4.2.2 "Memory-Efficient Gradient Computation", Alg. 3 "In-place Backward for
- * Log-Softmax Loss"): for every row r (one token position of one training-time-test step) with
- * logits z[r, 0..V), target distribution p[r, 0..V) and upstream gradient g[r],
- *     s  = sum_v p[r,v] * g[r]
- *     pi = softmax(z[r, :])
- *     z[r,v] <- -(p[r,v] * g[r] - pi[v] * s)
- * i.e. the gradient of  -g[r] * sum_v p[r,v] * log softmax(z[r,:])[v]  with respect to the logits,
- * written over the logits: no gradient buffer of the size of the logits exists.  g is one fp32
+ * Operation (Sec. 4.2.2 "Memory-Efficient Gradient Computation", Alg. 3): for every row r (one token
+ * position of one training-time-test step) with logits z[r, 0..V), target weights p[r, 0..V) and
+ * upstream gradient g[r], the gradient of the loss  -g[r] * sum_v p[r,v] * log softmax(z[r,:])[v]
+ * with respect to the logits,
+ *     softmax(z[r,:])[v] * g[r] * sum_u p[r,u]  -  g[r] * p[r,v],
+ * is written over the logits: no gradient buffer of the size of the logits exists.  g is one fp32
  * value per row (loss weight / position mask times the upstream scalar; rows with g = 0 become
  * exactly zero); p need not be normalised.
  *

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -123,7 +124,7 @@ struct ProfileRecord {
     hipEvent_t start, stop;
 };
 std::mutex g_prof_mutex;
-bool g_prof_on = false;
+std::atomic<bool> g_prof_on{false};   // read by every launch, written under g_prof_mutex
 std::vector<ProfileRecord> g_prof_records;
 thread_local ProfileRecord g_prof_open = {nullptr, nullptr, nullptr};
 
@@ -133,7 +134,7 @@ namespace ttt {
 
 void profile_begin(const char* kernel_name, hipStream_t stream) {
     g_prof_open.name = nullptr;
-    if (!g_prof_on) return;
+    if (!g_prof_on.load(std::memory_order_relaxed)) return;
     hipEvent_t a, b;
     if (hipEventCreate(&a) != hipSuccess) return;
     if (hipEventCreate(&b) != hipSuccess) {
@@ -194,8 +195,8 @@ extern "C" {
 
 int ttt_attn_profile_enable(int on) {
     std::lock_guard<std::mutex> lock(g_prof_mutex);
-    const int was = g_prof_on ? 1 : 0;
-    g_prof_on = on != 0;
+    const int was = g_prof_on.load() ? 1 : 0;
+    g_prof_on.store(on != 0);
     return was;
 }
 

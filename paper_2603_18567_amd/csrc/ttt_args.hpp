@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "ttt_device.hpp"
 
 namespace ttt {
@@ -74,6 +76,36 @@ hipError_t launch_loss_bwd(int dtype, void* logits, const void* target, const fl
 hipError_t launch_qkv_rope(const void* x, const void* w, const float* cos_tab, const float* sin_tab, const int* pos, void* q,
                            void* k, void* v, int64_t tokens, int hidden_in, int n_q, int n_k, int n_v, int64_t x_st,
                            int64_t w_st, int n_pos, hipStream_t stream);
+
+// Per-device host-side state of the launchers.  A kernel's opt-in to more than 48 KB of dynamic LDS
+// is an attribute of (kernel, device): LdsOptIn sets it the first time a kernel instantiation is
+// launched on each device (one bit per device index; indices past 63 simply set it every time).
+struct LdsOptIn {
+    std::atomic<uint64_t> done{0};
+    hipError_t ensure(const void* kernel, int bytes) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const bool tracked = dev >= 0 && dev < 64;
+        if (tracked && ((done.load(std::memory_order_acquire) >> dev) & 1u)) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e == hipSuccess && tracked) done.fetch_or((uint64_t)1 << dev, std::memory_order_release);
+        return e;
+    }
+};
+// compute units of the current device (cached per device index; 256 if the runtime reports none)
+inline hipError_t current_device_cu_count(int& n_cu) {
+    static std::atomic<int> cache[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < 64;
+    if (tracked && (n_cu = cache[dev].load(std::memory_order_relaxed)) > 0) return hipSuccess;
+    if ((e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    if (n_cu <= 0) n_cu = 256;
+    if (tracked) cache[dev].store(n_cu, std::memory_order_relaxed);
+    return hipSuccess;
+}
 
 // Diagnostics (off by default): brackets one kernel launch with HIP events on its stream so that
 // a caller can read per-kernel durations afterwards (ttt_attn_profile_totals).

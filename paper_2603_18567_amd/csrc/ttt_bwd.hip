@@ -144,8 +144,8 @@ template <int LPR> TTT_DEV float group_sum_dpp(float v) {
 
 // The same work for 16-bit types and at most KMAX steps, reading every Q_j, dO_j, O_j row exactly
 // once: the K_l, V_l rows of this (token, kv head) and their fp32 gradients stay in registers while
-// one sweep over (step, head of the group) feeds all of them (the diagonal part of Eq. (6)'s
-// backward: key (l, i) is seen only by the queries (j >= l, i)).
+// one sweep over (step, head of the group) feeds all of them (the suffix part of Alg. 2 read from the
+// key's side: key (l, i) is seen only by the queries (j >= l, i) of Sec. 2.4's unrolled steps).
 template <typename T, int D, int KMAX>
 __global__ __launch_bounds__(256) void ttt_bwd_pre_regs_kernel(const BwdArgs a) {
     static_assert(sizeof(T) == 2, "register budget sized for 16-bit elements");
@@ -441,16 +441,18 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_kernel(const BwdArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// dQ: query-stationary, software-pipelined (16-bit element types)
+// dQ: query-stationary, 128-row kv tiles (16-bit element types)
 //
 // One wave = 32 query rows with Q and dO as stationary B operands; a kv tile has 128 rows = 4
-// blocks of 32.  While the vector ALU turns the scores of block b into dS^T (two elements after
-// every matrix instruction), the matrix core accumulates dQ^T += K^T dS^T of block b-1.
+// blocks of 32, each taken through S^T, dP^T, dS^T and the dQ^T update in turn, with the LDS
+// fragments of the next matrix instructions requested ahead.  Eight waves (two per SIMD) overlap
+// one wave's vector work with the other's matrix work.
 // LDS: two stages of [K tile | V tile]; the stage bit is bit 16 of the per-lane addresses.
 // ------------------------------------------------------------------------------------------------
 template <typename T, int D, int NW>
 __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs a) {
-    static_assert(sizeof(T) == 2, "pipelined dQ kernel is for 16-bit elements");
+    static_assert(sizeof(T) == 2, "this dQ kernel is for 16-bit elements");
+    static_assert(NW == 8, "two waves per SIMD supply the overlap; no other wave count is built");
     using E = Elem<T>;
     using frag = typename E::frag;
     using TL = Tile<T, D>;
@@ -464,8 +466,8 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
     constexpr int STAGE_BYTES = 1 << 16;
     static_assert(2 * TILE_BYTES <= STAGE_BYTES, "stage layout");
     constexpr int NE = 2 * DB;   // matrix instructions of one dQ block update
-    constexpr int PDR = NW == 8 ? 2 : 3;
-    constexpr int PDT = NW == 8 ? 2 : (4 < NE ? 4 : NE);
+    constexpr int PDR = 2;       // row-wise K / V fragments requested ahead of their matrix instruction
+    constexpr int PDT = 2;       // K^T fragments requested ahead
     typedef __attribute__((address_space(3))) char lds_char;
 
     extern __shared__ __align__(16) char smem[];
@@ -592,50 +594,7 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
                     pacc = mma(va[t], gof[t], pacc);
                 }
             };
-            auto fused = [&](auto do_c, auto do_e, auto masked, int kb) {
-                constexpr bool DO_C = decltype(do_c)::value != 0;
-                constexpr bool DO_E = decltype(do_e)::value != 0;
-                constexpr bool MASK = decltype(masked)::value != 0;
-                const int eb = DO_C ? kb - 1 : kb;
-                if constexpr (DO_E) {
-#pragma unroll
-                    for (int x = 0; x < PDT; ++x) tfr[x] = ld_ktr(eb, x);
-                }
-                constexpr int GS = 2;            // matrix instructions per group
-                constexpr int NG = NE / GS;      // groups
-                constexpr int EPG = 16 / NG;     // elements per group
-#pragma unroll
-                for (int y = 0; y < NG; ++y) {
-                    if constexpr (DO_E) {
-#pragma unroll
-                        for (int x = GS * y + PDT; x < GS * y + PDT + GS; ++x)
-                            if (x < NE) tfr[x] = ld_ktr(eb, x);
-                    }
-                    issue_fence();
-                    if constexpr (DO_E) {
-#pragma unroll
-                        for (int x = GS * y; x < GS * y + GS; ++x) dqacc[x % DB] = mma(tfr[x], sfr[x / DB], dqacc[x % DB]);
-                    }
-                    if constexpr (DO_C) {
-#pragma unroll
-                        for (int x = EPG * y; x < EPG * y + EPG; ++x) {
-                            float p = fast_exp2(fmaf(sacc[x], c, -lse2));
-                            if constexpr (MASK) {
-                                const int kv = kv0 + kb * 32 + acc_row(x, hh);
-                                p = (kv <= qi && kv >= st) ? p : 0.f;
-                            }
-                            pacc[x] = p * (pacc[x] - dl);   // dS^T
-                        }
-                    }
-                }
-                issue_fence();
-                if constexpr (DO_C) {
-                    sfr[0] = acc_chunk<T>(pacc, 0);
-                    sfr[1] = acc_chunk<T>(pacc, 1);
-                }
-            };
-
-            if constexpr (NW == 8) {
+            {
                 // Two waves per SIMD: no pipelining inside the wave.  One wave's vector work runs
                 // while the other wave of the SIMD uses the matrix core (they fall into opposite
                 // phases by themselves); blocks that this wave's rows cannot see are skipped.
@@ -677,23 +636,6 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dq_pipe_kernel(const BwdArgs 
                         dqacc[x % DB] = mma(tfr[x], sfr[x / DB], dqacc[x % DB]);
                     }
                 }
-            } else {
-                prime_rows(0);
-#pragma unroll
-                for (int kb = 0; kb < NB; ++kb) {
-                    score(kb);
-                    if (kb + 1 < NB) prime_rows(kb + 1);
-                    const int kb0 = kv0 + kb * 32;
-                    const bool need_mask = kb0 + 31 > wq0 || kb0 < st_hi;
-                    if (kb == 0) {
-                        if (need_mask) fused(IntC<1>{}, IntC<0>{}, IntC<1>{}, kb);
-                        else fused(IntC<1>{}, IntC<0>{}, IntC<0>{}, kb);
-                    } else {
-                        if (need_mask) fused(IntC<1>{}, IntC<1>{}, IntC<1>{}, kb);
-                        else fused(IntC<1>{}, IntC<1>{}, IntC<0>{}, kb);
-                    }
-                }
-                fused(IntC<0>{}, IntC<1>{}, IntC<0>{}, NB - 1);
             }
         }
 #pragma unroll
@@ -916,36 +858,17 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_kernel(const BwdArgs a) {
             for (int qb = 0; qb < QTL / 32; ++qb) {
                 const int qb0 = q0 + qb * 32;
                 if (qb0 + 31 < wk0 || qb0 >= wq_end) continue;
-                // bf16: all LDS reads of the block are issued up front (row-wise fragments for S and
-                // dP, transposed ones for dV and dK) so that their latency hides behind the matrix
-                // work; fp32 fragments are twice as large and are read where they are used
-                constexpr bool kUpfront = sizeof(T) == 2;
+                // fragments are read where they are used (this kernel serves the fp32 instantiation;
+                // 16-bit types take ttt_bwd_dkv_p8_kernel)
                 frag qa[DC], ga[DC], gt[2][DB], qt[2][DB];
-                if constexpr (kUpfront) {
-#pragma unroll
-                    for (int t = 0; t < DC; ++t) {
-                        qa[t] = frag_rowwise<T, D>(tq, qb * 32 + n, t * 16 + hh * 8);
-                        ga[t] = frag_rowwise<T, D>(tg, qb * 32 + n, t * 16 + hh * 8);
-                    }
-#pragma unroll
-                    for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-                        for (int db = 0; db < DB; ++db) {
-                            gt[c2][db] = frag_transposed<T, D>(tg, qb * 32 + c2 * 16, db * 32, lane);
-                            qt[c2][db] = frag_transposed<T, D>(tq, qb * 32 + c2 * 16, db * 32, lane);
-                        }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
                 // S[q, kv] = Q K^T and dP[q, kv] = dO V^T : lane = kv column, values = query rows
                 f32x16 sacc, pacc;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sacc[i] = pacc[i] = 0.f;
 #pragma unroll
                 for (int t = 0; t < DC; ++t) {
-                    if constexpr (!kUpfront) {
-                        qa[t] = frag_rowwise<T, D>(tq, qb * 32 + n, t * 16 + hh * 8);
-                        ga[t] = frag_rowwise<T, D>(tg, qb * 32 + n, t * 16 + hh * 8);
-                    }
+                    qa[t] = frag_rowwise<T, D>(tq, qb * 32 + n, t * 16 + hh * 8);
+                    ga[t] = frag_rowwise<T, D>(tg, qb * 32 + n, t * 16 + hh * 8);
                     sacc = mma(qa[t], kf[t], sacc);
                     pacc = mma(ga[t], vf[t], pacc);
                 }
@@ -976,10 +899,8 @@ __global__ __launch_bounds__(NW * 64) void ttt_bwd_dkv_kernel(const BwdArgs a) {
                     const frag sf = acc_chunk<T>(pacc, c2);
 #pragma unroll
                     for (int db = 0; db < DB; ++db) {
-                        if constexpr (!kUpfront) {
-                            gt[c2][db] = frag_transposed<T, D>(tg, qb * 32 + c2 * 16, db * 32, lane);
-                            qt[c2][db] = frag_transposed<T, D>(tq, qb * 32 + c2 * 16, db * 32, lane);
-                        }
+                        gt[c2][db] = frag_transposed<T, D>(tg, qb * 32 + c2 * 16, db * 32, lane);
+                        qt[c2][db] = frag_transposed<T, D>(tq, qb * 32 + c2 * 16, db * 32, lane);
                         dvacc[db] = mma(pf, gt[c2][db], dvacc[db]);
                         dkacc[db] = mma(sf, qt[c2][db], dkacc[db]);
                     }
@@ -1476,7 +1397,7 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         if constexpr (sizeof(T) == 2) in_regs = geo.step_begin + geo.n_steps <= KREG;
         if (in_regs) {
             if constexpr (sizeof(T) == 2) {
-                ProfileScope prof("ttt_bwd_pre_kernel", stream);
+                ProfileScope prof("ttt_bwd_pre_regs_kernel", stream);
                 hipLaunchKernelGGL((ttt_bwd_pre_regs_kernel<T, D, KREG>), dim3((unsigned)grid), dim3(256), 0, stream, a);
             }
         } else {
@@ -1500,12 +1421,8 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         const void* kern;
         if constexpr (kPipe) kern = (const void*)ttt_bwd_dq_pipe_kernel<T, D, NWQ>;
         else kern = (const void*)ttt_bwd_dq_kernel<T, D, QB_DQ, NW_DQ>;
-        static bool attr_done = false;
-        if (!attr_done) {
-            e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        static LdsOptIn lds_opt_in;
+        if ((e = lds_opt_in.ensure(kern, LDS)) != hipSuccess) return e;
         // the pipelined kernel addresses the pieces of up to 64 rows of K or V with 32-bit byte offsets
         if (kPipe && geo.kv_st * 64 * (int64_t)sizeof(T) >= (int64_t)1 << 32) return hipErrorInvalidValue;
         a.n_tiles = (geo.T + QT - 1) / QT;
@@ -1513,7 +1430,7 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         set_head_map(a.map, geo.hkv, a.n_tiles * geo.n_steps * geo.G, grid);
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
         {
-            ProfileScope prof("ttt_bwd_dq_kernel", stream);
+            ProfileScope prof(kPipe ? "ttt_bwd_dq_pipe_kernel" : "ttt_bwd_dq_kernel", stream);
             if constexpr (kPipe)
                 hipLaunchKernelGGL((ttt_bwd_dq_pipe_kernel<T, D, NWQ>), dim3((unsigned)grid), dim3(NWQ * 64), LDS, stream, a);
             else
@@ -1531,12 +1448,8 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         const void* kern;
         if constexpr (kWs) kern = (const void*)ttt_bwd_dkv_p8_kernel<T, D>;
         else kern = (const void*)ttt_bwd_dkv_kernel<T, D, NW_KV>;
-        static bool attr_done = false;
-        if (!attr_done) {
-            e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-            if (e != hipSuccess) return e;
-            attr_done = true;
-        }
+        static LdsOptIn lds_opt_in;
+        if ((e = lds_opt_in.ensure(kern, LDS)) != hipSuccess) return e;
         // that kernel addresses the rows of a 32-row block with 32-bit byte offsets
         if (kWs && geo.q_st * 32 * (int64_t)sizeof(T) >= (int64_t)1 << 32) return hipErrorInvalidValue;
         a.n_tiles = (geo.T + KVT - 1) / KVT;
@@ -1556,13 +1469,8 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
             // One workgroup fills a compute unit and costs about its number of (step, head) pairs, so the
             // sweep takes rounds x pairs-per-workgroup, plus a start and a flush of the sums per round:
             // take the split for which that is least.
-            static int n_cu = 0;
-            if (n_cu == 0) {
-                int dev = 0;
-                if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-                if ((e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-                if (n_cu <= 0) n_cu = 256;
-            }
+            int n_cu = 0;
+            if ((e = current_device_cu_count(n_cu)) != hipSuccess) return e;
             double best = 0.;
             for (int ns = 1; ns <= n_jh; ++ns) {
                 const int64_t wgs = (int64_t)n_units * geo.hkv * ns;
@@ -1580,7 +1488,7 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         set_head_map(a.map, geo.hkv, n_units * n_split, grid);
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
         {
-            ProfileScope prof("ttt_bwd_dkv_kernel", stream);
+            ProfileScope prof(kWs ? "ttt_bwd_dkv_p8_kernel" : "ttt_bwd_dkv_kernel", stream);
             if constexpr (kWs)
                 hipLaunchKernelGGL((ttt_bwd_dkv_p8_kernel<T, D>), dim3((unsigned)grid), dim3(512), LDS, stream, a);
             else

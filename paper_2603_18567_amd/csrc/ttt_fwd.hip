@@ -387,13 +387,8 @@ template <typename T, int D, int QB, int NW, int MINB> struct FwdCfg {
 template <typename T, int D, int QB, int NW, int MINB> static hipError_t launch_fwd_t(FwdArgs& a, hipStream_t stream) {
     using C = FwdCfg<T, D, QB, NW, MINB>;
     auto kern = ttt_fwd_kernel<T, D, QB, NW, MINB>;
-    static bool attr_done = false;   // benign race: the attribute is idempotent
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           C::kLds + (sizeof(T) == 2 ? C::kDiagLds : 0));
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static LdsOptIn lds_opt_in;
+    if (hipError_t e = lds_opt_in.ensure((const void*)kern, C::kLds + (sizeof(T) == 2 ? C::kDiagLds : 0)); e != hipSuccess) return e;
     const Geometry& geo = a.geo;
     // as many heads of a kv group per workgroup as divide both the group and the waves (at most 4:
     // a workgroup keeps at least 64 rows)

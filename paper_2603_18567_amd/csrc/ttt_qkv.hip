@@ -208,12 +208,8 @@ static hipError_t launch_qkv_rope_t(QkvArgs& a, hipStream_t stream) {
     constexpr int MT = MB * 128;
     constexpr int LDS = 2 * (MT + 256) * 64 * 2;
     auto kern = ttt_qkv_rope_kernel<T, MB>;
-    static bool attr_done = false;   // benign race: the attribute is idempotent
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static LdsOptIn lds_opt_in;
+    if (hipError_t e = lds_opt_in.ensure((const void*)kern, LDS); e != hipSuccess) return e;
     a.m_tiles = (a.T + MT - 1) / MT;
     // blocks of 4 x 8 tiles, dealt out to the 8 XCDs in turn: 32 slots per block and XCD
     const int64_t blocks = (int64_t)((a.m_tiles + 3) / 4) * ((a.n_tiles + 7) / 8);
@@ -252,14 +248,8 @@ hipError_t launch_qkv_rope(const void* x, const void* w, const float* cos_tab, c
     a.n_tiles = ((n_q + n_k + n_v) * 128 + 255) / 256;
     // Token tile of 256 or 128 rows: one workgroup per compute unit at a time, so the call takes
     // rounds x tile time; the small tile costs a little more than half of the large one.
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0;
-        hipError_t e;
-        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-        if ((e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-        if (n_cu <= 0) n_cu = 256;
-    }
+    int n_cu = 0;
+    if (hipError_t e = current_device_cu_count(n_cu); e != hipSuccess) return e;
     const int64_t big = ((tokens + 255) / 256) * a.n_tiles, small = ((tokens + 127) / 128) * a.n_tiles;
     const double cost_big = (double)((big + n_cu - 1) / n_cu) * 1.0, cost_small = (double)((small + n_cu - 1) / n_cu) * kSmallTileCost;
     const bool use_small = cost_small < cost_big;

@@ -66,7 +66,9 @@ def test_uniform_logits_closed_form_with_unnormalised_target():
     p = np.arange(1, v + 1, dtype=np.float64)[None, :] / 7.0      # sums to 13, not 1
     g = np.array([0.5])
     out = logsoftmax_loss_bwd(np.full((1, v), 4.0), p, g)
-    np.testing.assert_allclose(out, -(p * 0.5 - (p.sum() * 0.5) / v), rtol=1e-13)
+    # element 7 is the difference of two equal terms of size 0.5: exact zero in the closed form, one
+    # rounding of exp(log(1/13)) in the oracle, hence the absolute floor of a few ulps of 0.5
+    np.testing.assert_allclose(out, -(p * 0.5 - (p.sum() * 0.5) / v), rtol=1e-13, atol=1e-15)
 
 
 def test_central_finite_differences_of_the_loss():
