@@ -412,6 +412,9 @@ static int bwd_slice(const ttt_attn_params* p, const Slice& sl, const void* cons
     }
     a.tok_start = tok_start;
     a.tok_end = tok_end;
+    a.cu_host = cu_host + sl.doc0;
+    a.cu_base = cu_host[sl.doc0];
+    a.n_docs = sl.n_docs;
     a.delta = reinterpret_cast<float*>(ws + L.delta);
     a.lse2 = reinterpret_cast<float*>(ws + L.lse2);
     a.dk0_acc = reinterpret_cast<float*>(ws + L.dk0);

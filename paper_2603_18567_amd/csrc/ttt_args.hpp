@@ -64,6 +64,10 @@ struct BwdArgs {
     int n_units;            // dK/dV kernel (16-bit): (key tile, query chunk) units per kv head and split
     int chunk_blocks;       // dK/dV kernel (16-bit): 32-row query blocks per chunk (a multiple of 4)
     HeadMap map;
+    // host side only (the launchers' work-split model reads the document structure from it)
+    const int32_t* cu_host; // cu_seqlens of the documents of this call: n_docs + 1 entries, first entry = cu_base
+    int cu_base;
+    int n_docs;
 };
 
 // launchers (defined in the kernel files); all enqueue on `stream` and return the launch status

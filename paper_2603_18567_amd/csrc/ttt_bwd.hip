@@ -13,6 +13,12 @@
 //                        through LDS; partial sums of the (step, head) splits meet in fp32 atomics
 //                        (ttt_bwd_dkv_p8_kernel: eight equal waves, for 16-bit types).
 //   ttt_bwd_finish_kernel  fp32 block-0 sums -> dK_0, dV_0 in the tensor dtype.
+#include <algorithm>
+#include <functional>
+#include <mutex>
+#include <queue>
+#include <vector>
+
 #include "ttt_args.hpp"
 
 namespace ttt {
@@ -1370,6 +1376,116 @@ static void set_head_map(HeadMap& m, int hkv, int rest_count, int64_t& grid) {
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Work split of the eight-wave dK/dV kernel: 32-row query blocks per chunk and ways to split the
+// (step, head) list, chosen by a model of the launch.
+//
+// One workgroup fills a compute unit and handles one unit = (128-key tile, chunk, split).  Measured
+// on MI355X (sweeps over chunk size and split at 2048 / 4096 / 16384 tokens, all steps and one step
+// per call): a unit costs about 1.9 us per step (one 32-row query block per wave group and (step,
+// head) pair) plus about 13 us of its own (workgroup launch, the K_0/V_0 tile and first query block
+// arriving, the flush of its sums through LDS and fp32 atomics), and an empty unit (a tile that no
+// row of the chunk sees) about 1 us.  The model deals one kv head's units, in launch order, to the
+// head's share of the compute units (each to the one that frees up first) and takes the
+// combination with the shortest finish time; it reproduces the sweeps within 10 % and their
+// ranking.  Short (step, head) lists -- one step per call -- want long chunks (few units, little
+// flushing), long lists want the 512-row chunks whose units of one XCD stay together.
+// ------------------------------------------------------------------------------------------------
+struct DkvPlan {
+    int chunk_blocks, n_split, n_units;
+};
+
+static int dkv_units_of(int T, int n_tiles, int chunk_blocks) {
+    const int n_chunks = (T + chunk_blocks * 32 - 1) / (chunk_blocks * 32);
+    int n = 0;
+    for (int ch = 0; ch < n_chunks; ++ch) n += std::min(n_tiles, (ch + 1) * chunk_blocks / 4);
+    return n;
+}
+
+static DkvPlan plan_dkv_split(const BwdArgs& a, int n_jh, int n_cu) {
+    const Geometry& geo = a.geo;
+    const int T = geo.T;
+    const int n_tiles = (T + 127) / 128;
+    constexpr double kStepUs = 1.9, kUnitUs = 13.0, kEmptyUs = 1.0;
+    // one entry per distinct request: the plan depends on the document structure, the list length and the device
+    struct Key {
+        int T, n_docs, n_jh, hkv, n_cu;
+        uint64_t cu_hash;
+        bool operator==(const Key& o) const {
+            return T == o.T && n_docs == o.n_docs && n_jh == o.n_jh && hkv == o.hkv && n_cu == o.n_cu && cu_hash == o.cu_hash;
+        }
+    };
+    uint64_t h = 1469598103934665603ull;
+    for (int r = 0; r <= a.n_docs; ++r) h = (h ^ (uint64_t)(uint32_t)(a.cu_host[r] - a.cu_base)) * 1099511628211ull;
+    const Key key{T, a.n_docs, n_jh, geo.hkv, n_cu, h};
+    static std::mutex mu;
+    static std::vector<std::pair<Key, DkvPlan>> cache;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        for (const auto& e : cache)
+            if (e.first == key) return e.second;
+    }
+    // last query row (+1) that sees the last key of each tile: the end of that key's document
+    std::vector<int> q_end(n_tiles);
+    {
+        int r = 0;
+        for (int t = 0; t < n_tiles; ++t) {
+            const int key_tok = std::min(t * 128 + 127, T - 1);
+            while (r + 1 < a.n_docs && a.cu_host[r + 1] - a.cu_base <= key_tok) ++r;
+            q_end[t] = a.cu_host[r + 1] - a.cu_base;
+        }
+    }
+    const int cus = std::max(1, n_cu / geo.hkv);   // a kv head's share of the device
+    DkvPlan best{16, 1, 0};
+    double best_us = -1.;
+    std::vector<int> nqb2;
+    for (int cb : {16, 32, 64}) {
+        const int n_chunks = (T + cb * 32 - 1) / (cb * 32);
+        nqb2.clear();
+        for (int ch = 0; ch < n_chunks; ++ch) {
+            const int tiles = std::min(n_tiles, (ch + 1) * cb / 4);
+            for (int t = 0; t < tiles; ++t) {
+                const int qb_lo = std::max(t * 4, ch * cb);
+                const int nqb = std::min((q_end[t] - 1) / 32, (ch + 1) * cb - 1) - qb_lo + 1;
+                nqb2.push_back(nqb > 0 ? (nqb + 1) / 2 : 0);
+            }
+        }
+        for (int ns : {1, 2, 3, 4, 6, 8}) {
+            if (ns > n_jh) break;
+            double finish = 0.;
+            if ((int64_t)nqb2.size() * ns <= 8192) {
+                std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+                for (int c = 0; c < cus; ++c) free_at.push(0.);
+                for (int sp = 0; sp < ns; ++sp) {
+                    const int n_c = (n_jh - sp + ns - 1) / ns;
+                    for (int u : nqb2) {
+                        const double t0 = free_at.top();
+                        free_at.pop();
+                        const double t1 = t0 + (u > 0 ? (double)n_c * u * kStepUs + kUnitUs : kEmptyUs);
+                        free_at.push(t1);
+                        finish = std::max(finish, t1);
+                    }
+                }
+            } else {   // very many units: the tail does not matter, the work and the per-unit cost do
+                double work = 0., longest = 0.;
+                for (int u : nqb2) {
+                    work += u > 0 ? (double)n_jh * u * kStepUs + ns * kUnitUs : ns * kEmptyUs;
+                    longest = std::max(longest, (double)((n_jh + ns - 1) / ns) * u * kStepUs + kUnitUs);
+                }
+                finish = work / cus + longest;
+            }
+            if (best_us < 0. || finish < best_us) {
+                best_us = finish;
+                best = DkvPlan{cb, ns, (int)nqb2.size()};
+            }
+        }
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (cache.size() >= 64) cache.erase(cache.begin());
+    cache.emplace_back(key, best);
+    return best;
+}
+
 template <typename T, int D, int QB_DQ, int NW_DQ, int NW_KV>
 static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
     const Geometry& geo = a.geo;
@@ -1458,28 +1574,13 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
         int n_split = 1;
         int n_units = a.n_tiles;   // units per kv head and split: key tiles, or (key tile, query chunk) pairs
         if constexpr (kWs) {
-            a.chunk_blocks = 16;
-            const int n_chunks = (geo.T + a.chunk_blocks * 32 - 1) / (a.chunk_blocks * 32);
-            n_units = 0;
-            for (int ch = 0; ch < n_chunks; ++ch) {
-                const int tiles = (ch + 1) * a.chunk_blocks / 4;
-                n_units += tiles < a.n_tiles ? tiles : a.n_tiles;
-            }
-            a.n_units = n_units;
-            // One workgroup fills a compute unit and costs about its number of (step, head) pairs, so the
-            // sweep takes rounds x pairs-per-workgroup, plus a start and a flush of the sums per round:
-            // take the split for which that is least.
             int n_cu = 0;
             if ((e = current_device_cu_count(n_cu)) != hipSuccess) return e;
-            double best = 0.;
-            for (int ns = 1; ns <= n_jh; ++ns) {
-                const int64_t wgs = (int64_t)n_units * geo.hkv * ns;
-                const double cost = (double)((wgs + n_cu - 1) / n_cu) * ((n_jh + ns - 1) / ns + 0.5);
-                if (ns == 1 || cost < best) {
-                    best = cost;
-                    n_split = ns;
-                }
-            }
+            const DkvPlan plan = plan_dkv_split(a, n_jh, n_cu);
+            a.chunk_blocks = plan.chunk_blocks;
+            n_split = plan.n_split;
+            n_units = dkv_units_of(geo.T, a.n_tiles, a.chunk_blocks);
+            a.n_units = n_units;
         } else {
             while (n_split < n_jh && (int64_t)n_units * geo.hkv * n_split < 2048) ++n_split;
         }
