@@ -37,6 +37,7 @@ struct QkvArgs {
     int n_q, n_k, n_v;    // heads written to q (rotated), k (rotated), v (as they are); weight rows in this order
     int64_t x_st, w_st;   // row strides in elements
     int m_tiles, n_tiles, per_xcd;
+    int n_first;          // first 256-feature tile of this launch (a call may be carried out as two launches)
 };
 
 template <typename T, int MB>
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(512) void ttt_qkv_rope_kernel(const QkvArgs a) {
     const int tm = (blk / blocks_n) * 4 + (in_blk >> 3), tn = (blk % blocks_n) * 8 + (in_blk & 7);
     if (tm >= a.m_tiles || tn >= a.n_tiles) return;
     const int m0 = tm * MT;
-    const int n0 = tn * NT;
+    const int n0 = (a.n_first + tn) * NT;
     const int n_feat = (a.n_q + a.n_k + a.n_v) * D;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -245,15 +246,38 @@ hipError_t launch_qkv_rope(const void* x, const void* w, const float* cos_tab, c
     a.n_pos = n_pos;
     a.x_st = x_st;
     a.w_st = w_st;
-    a.n_tiles = ((n_q + n_k + n_v) * 128 + 255) / 256;
-    // Token tile of 256 or 128 rows: one workgroup per compute unit at a time, so the call takes
-    // rounds x tile time; the small tile costs a little more than half of the large one.
+    const int n_tiles = ((n_q + n_k + n_v) * 128 + 255) / 256;
+    // One workgroup per compute unit at a time, so a launch takes rounds x tile time.  Token tiles of
+    // 256 rows are the efficient ones; a tile of 128 rows costs a little more than half of one.  The
+    // feature tiles are cut into a first part done with 256-row tiles and a rest done with 128-row
+    // tiles (either may be empty) so that both launches fill their last round: 4096 tokens x 6144
+    // features are 16 x 24 large tiles = one and a half rounds of 256; as 16 x 16 large tiles plus
+    // 32 x 8 small ones they are two full rounds costing 1 + 0.67.
     int n_cu = 0;
     if (hipError_t e = current_device_cu_count(n_cu); e != hipSuccess) return e;
-    const int64_t big = ((tokens + 255) / 256) * a.n_tiles, small = ((tokens + 127) / 128) * a.n_tiles;
-    const double cost_big = (double)((big + n_cu - 1) / n_cu) * 1.0, cost_small = (double)((small + n_cu - 1) / n_cu) * kSmallTileCost;
-    const bool use_small = cost_small < cost_big;
-    return use_small ? launch_qkv_rope_t<1>(a, stream) : launch_qkv_rope_t<2>(a, stream);
+    const int64_t m_big = (tokens + 255) / 256, m_small = (tokens + 127) / 128;
+    int best_nb = n_tiles;
+    double best_cost = -1.;
+    for (int nb = n_tiles; nb >= 0; --nb) {
+        const double cost = (double)((m_big * nb + n_cu - 1) / n_cu) * 1.0 +
+                            (double)((m_small * (n_tiles - nb) + n_cu - 1) / n_cu) * kSmallTileCost +
+                            (nb > 0 && nb < n_tiles ? 0.02 : 0.);   // a second launch is not free
+        if (best_cost < 0. || cost < best_cost - 1e-9) {
+            best_cost = cost;
+            best_nb = nb;
+        }
+    }
+    if (best_nb > 0) {
+        a.n_first = 0;
+        a.n_tiles = best_nb;
+        if (hipError_t e = launch_qkv_rope_t<2>(a, stream); e != hipSuccess) return e;
+    }
+    if (best_nb < n_tiles) {
+        a.n_first = best_nb;
+        a.n_tiles = n_tiles - best_nb;
+        if (hipError_t e = launch_qkv_rope_t<1>(a, stream); e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace ttt

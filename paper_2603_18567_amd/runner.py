@@ -8,8 +8,9 @@ from . import binding as B
 
 
 class TttAttnRunner:
-    def __init__(self, q, k, v, cu_seqlens, softmax_scale, device="cuda:0"):
-        """q: list of k [T,hq,d] tensors; k,v: lists of k [T,hkv,d] tensors (device); cu_seqlens: ints."""
+    def __init__(self, q, k, v, cu_seqlens, softmax_scale, device="cuda:0", allocate_outputs=True):
+        """q: list of k [T,hq,d] tensors; k,v: lists of k [T,hkv,d] tensors (device); cu_seqlens: ints.
+        allocate_outputs=False leaves o / lse to the caller (lists of k entries, None where not needed)."""
         self.dev = torch.device(device)
         self.q, self.k, self.v = q, k, v
         self.K = len(q)
@@ -18,8 +19,8 @@ class TttAttnRunner:
         self.scale = float(softmax_scale)
         T, hq, d = q[0].shape
         self.T, self.hq, self.d = T, hq, d
-        self.o = [torch.empty_like(x) for x in q]
-        self.lse = [torch.empty((hq, T), dtype=torch.float32, device=self.dev) for _ in q]
+        self.o = [torch.empty_like(x) for x in q] if allocate_outputs else None
+        self.lse = [torch.empty((hq, T), dtype=torch.float32, device=self.dev) for _ in q] if allocate_outputs else None
         self.dq = self.dk = self.dv = None
         self._ws = {}
 
