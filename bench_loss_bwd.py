@@ -21,6 +21,20 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0
 
 
+def recorded_traffic(summary_name):
+    """HBM bytes per launch of this script's kernel as the committed rocprofv3 summary of its default
+    command states them ("... MB read ... MB written"); (bytes or None, source file)."""
+    import re
+    path = os.path.join(ROOT, "profiles", summary_name)
+    if not os.path.exists(path):
+        return None, None
+    text = open(path).read()
+    rd, wr = re.search(r"([\d.]+) MB read", text), re.search(r"([\d.]+) MB written", text)
+    if not rd or not wr:
+        return None, os.path.relpath(path, ROOT)
+    return (float(rd.group(1)) + float(wr.group(1))) * 1e6, os.path.relpath(path, ROOT)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--rows", type=int, default=28672)
@@ -58,16 +72,15 @@ def main():
     esz = z.element_size()
     alg_bytes = args.rows * (3 * args.vocab * esz + 4)
     ach = alg_bytes / (k_ms * 1e-3) / 1e9 if k_ms else None
+    traffic, traffic_source = recorded_traffic("loss_bwd_28672x32000_kernel_stats.txt")
     out = {"metric": "loss_bwd_inplace_rows_per_s", "value": args.rows / (ms * 1e-3), "unit": "rows/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
            "config": {"workload": f"draft_logits_{args.rows}x{args.vocab}", "rows": args.rows, "vocab": args.vocab},
            "roofline": {"kernel": "ttt_loss_bwd_kernel", "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": ach / PEAK_HBM_GBS if ach else None,
-                        # recorded from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of the default command
-                        # (profiles/loss_bwd_28672x32000_kernel_stats.txt)
-                        "traffic": 7342.0e6 + 3670.0e6 if (args.rows, args.vocab, args.dtype) == (28672, 32000, "f32") else None,
-                        "avg_ms": k_ms,
+                        # parsed from the committed rocprofv3 summary of the default command, never typed in here
+                        "traffic": traffic if (args.rows, args.vocab, args.dtype) == (28672, 32000, "f32") else None, "traffic_source": traffic_source, "avg_ms": k_ms,
                         "algorithmic_bytes_per_launch": alg_bytes}}
     if not args.no_cpu_baseline:
         from oracle.loss_oracle import logsoftmax_loss_bwd

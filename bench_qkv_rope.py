@@ -23,6 +23,20 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = 2500.0
 
 
+def recorded_traffic(summary_name):
+    """HBM bytes per launch of this script's kernel as the committed rocprofv3 summary of its default
+    command states them ("... MB read ... MB written"); (bytes or None, source file)."""
+    import re
+    path = os.path.join(ROOT, "profiles", summary_name)
+    if not os.path.exists(path):
+        return None, None
+    text = open(path).read()
+    rd, wr = re.search(r"([\d.]+) MB read", text), re.search(r"([\d.]+) MB written", text)
+    if not rd or not wr:
+        return None, os.path.relpath(path, ROOT)
+    return (float(rd.group(1)) + float(wr.group(1))) * 1e6, os.path.relpath(path, ROOT)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--tokens", type=int, default=4096)
@@ -95,15 +109,15 @@ def main():
     uq, uk, uv = unfused()
     diff = max(float((uq.float() - q.float()).abs().max()), float((uk.float() - k.float()).abs().max()),
                float((uv.float() - v.float()).abs().max()))
+    traffic, traffic_source = recorded_traffic("qkv_rope_4096x8192x6144_kernel_stats.txt")
     out = {"metric": "qkv_rope_dense_tflops", "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": f"draft_qkv_{T}x{hin}x{nf}", "tokens": T, "hidden_in": hin, "hq": hq, "hkv": hkv, "head_dim": d},
            "roofline": {"kernel": "ttt_qkv_rope_kernel", "bound": "mfma", "achieved": ach, "peak": PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": ach / PEAK_TFLOPS if ach else None,
-                        # recorded from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of the default command
-                        # (profiles/qkv_rope_4096x8192x6144_kernel_stats.txt)
-                        "traffic": 628.9e6 + 97.6e6 if (T, hin, hq, hkv) == (4096, 8192, 32, 8) else None, "avg_ms": k_ms,
+                        # parsed from the committed rocprofv3 summary of the default command, never typed in here
+                        "traffic": traffic if (T, hin, hq, hkv) == (4096, 8192, 32, 8) else None, "traffic_source": traffic_source, "avg_ms": k_ms,
                         "algorithmic_flops_per_launch": flops},
            "unfused_comparison": {"vendor_gemm_plus_rotation_ms": unf_ms, "vendor_gemm_alone_ms": gemm_ms,
                                   "vendor_gemm_alone_tflops": flops / (gemm_ms * 1e-3) / 1e12,
