@@ -12,7 +12,8 @@ on one batch of seeded synthetic inputs already resident in HBM.  Prints ONE JSO
   pct_of_measured_clock_peak   against CU count x 4096 flop/clk x the shader clock the driver
                         reports while the same steps run back to back (a separate, untimed leg);
   step_at_a_time        the training order (Sec. 2.4: step j's input depends on step j-1): k forward
-                        calls, then k backward calls in descending order with the fp32 carry;
+                        calls, then k backward calls in descending order with the fp32 carry; also the
+                        same calls replayed from one captured HIP graph;
   roofline              of the dominant kernel, from per-kernel HIP-event times (library
                         diagnostics) taken in a separate, untimed pass over the same steps;
   configs               ms / TFLOP/s / % of peak of the five configurations beside the headline one;
@@ -302,6 +303,21 @@ def main():
         out["step_at_a_time"] = {"ms": sw_ms, "median_ms": statistics.median(sw_spans), "min_ms": min(sw_spans),
                                  "tflops": sw_val, "pct_of_peak": 100.0 * sw_val / peak,
                                  "calls": f"{wl.k} forward + {wl.k} backward (accumulate_dkv=1, descending steps)"}
+        # the same 2k calls recorded once in a HIP graph and replayed (the library allocates nothing and
+        # never synchronises, so its calls can be captured): what the host-side launches cost
+        try:
+            graph = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.graph(graph, stream=side):
+                b.stepwise()
+            torch.cuda.synchronize()
+            g_ms, g_spans = b.timed(graph.replay, args.steps, 2)
+            out["step_at_a_time"]["graph_replay_ms"] = g_ms
+            out["step_at_a_time"]["graph_replay_median_ms"] = statistics.median(g_spans)
+        except RuntimeError as err:       # capture refused by the runtime: reported, not fatal
+            out["step_at_a_time"]["graph_replay_ms"] = None
+            out["step_at_a_time"]["graph_replay_error"] = str(err)[:200]
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, b.inp, args.cpu_rows)
