@@ -47,6 +47,7 @@ SMALL = [
     custom_workload("bf16_gqa3", "bf16", [300, 45, 600], 6, 2, 128, 3, 25),        # 3 query heads per kv head: no head packing
     custom_workload("bf16_hkv3", "bf16", [420, 130], 6, 3, 128, 3, 26),            # hkv neither divides nor is divided by 8
     custom_workload("bf16_hkv5", "bf16", [777], 10, 5, 128, 4, 27),                # the same with an odd head count, 7 key tiles
+    custom_workload("bf16_g16", "bf16", [390, 260], 64, 4, 128, 3, 28),            # 16 query heads per kv head (the 235B shape's grouping)
 ]
 
 
