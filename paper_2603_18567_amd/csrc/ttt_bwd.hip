@@ -1520,10 +1520,15 @@ static hipError_t launch_bwd_t(BwdArgs& a, hipStream_t stream) {
 
     // 1. clear the block-0 accumulators unless a carry from later steps is being continued
     if (!a.accumulate || a.carry_reset) {
-        const int blocks = (int)((acc_n4 + 255) / 256 < 4096 ? (acc_n4 + 255) / 256 : 4096);
         ProfileScope prof("ttt_fill_zero_kernel", stream);
-        hipLaunchKernelGGL(ttt_fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<f32x4*>(a.dk0_acc), acc_n4);
-        hipLaunchKernelGGL(ttt_fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<f32x4*>(a.dv0_acc), acc_n4);
+        // the two accumulators follow each other in the workspace (the second one 256-byte aligned):
+        // one launch clears both when nothing lies between them
+        const bool adjacent = a.dv0_acc == a.dk0_acc + 4 * acc_n4;
+        const int64_t n4 = adjacent ? 2 * acc_n4 : acc_n4;
+        const int blocks = (int)((n4 + 255) / 256 < 8192 ? (n4 + 255) / 256 : 8192);
+        hipLaunchKernelGGL(ttt_fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<f32x4*>(a.dk0_acc), n4);
+        if (!adjacent)
+            hipLaunchKernelGGL(ttt_fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<f32x4*>(a.dv0_acc), n4);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
 
