@@ -11,6 +11,7 @@ on one batch of seeded synthetic inputs already resident in HBM.  Prints ONE JSO
   bwd_8dP_tflops        the backward under the no-recompute convention (8*d*pairs);
   pct_of_measured_clock_peak   against CU count x 4096 flop/clk x the shader clock the driver
                         reports while the same steps run back to back (a separate, untimed leg);
+  sustained_power_w / power_cap_w / energy_per_step_j   board power over that leg, the board's cap;
   step_at_a_time        the training order (Sec. 2.4: step j's input depends on step j-1): k forward
                         calls, then k backward calls in descending order with the fp32 carry; also the
                         same calls replayed from one captured HIP graph;
@@ -81,9 +82,26 @@ class ClockSampler(threading.Thread):
         super().__init__(daemon=True)
         files = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
         self.path = files[0] if files else None
+        power = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        self.power_path = power[0] if power else None          # board power, microwatts
         self.period = period
         self.samples = []
+        self.power_samples = []
         self.stop_flag = False
+
+    @staticmethod
+    def read_number(path):
+        try:
+            with open(path) as f:
+                return float(f.read().strip())
+        except (OSError, ValueError, TypeError):
+            return None
+
+    def power_cap_w(self):
+        if not self.power_path:
+            return None
+        v = self.read_number(self.power_path.replace("power1_input", "power1_cap"))
+        return v / 1e6 if v else None
 
     def read_once(self):
         try:
@@ -100,6 +118,10 @@ class ClockSampler(threading.Thread):
             v = self.read_once()
             if v:
                 self.samples.append(v)
+            if self.power_path:
+                w = self.read_number(self.power_path)
+                if w:
+                    self.power_samples.append(w / 1e6)
             time.sleep(self.period)
 
 
@@ -296,6 +318,12 @@ def main():
         else:
             out["sustained_clock_mhz"] = None
             out["pct_of_measured_clock_peak"] = None
+        # board power over the same leg (the driver's hwmon reading) beside the board's cap: these
+        # kernels run against the cap, so a step's time is its energy divided by the cap
+        phalf = sampler.power_samples[len(sampler.power_samples) // 2:]
+        out["sustained_power_w"] = statistics.median(phalf) if phalf else None
+        out["power_cap_w"] = sampler.power_cap_w()
+        out["energy_per_step_j"] = out["sustained_power_w"] * ms_per_step * 1e-3 if phalf else None
 
         # ---- the training order: k forward calls, then k backward calls (descending, fp32 carry)
         sw_ms, sw_spans = b.timed(b.stepwise, args.steps, max(2, args.warmup // 2))
