@@ -117,6 +117,19 @@ def one_point(args, k, S):
            "ours_ms": ours_ms, "ours_useful_tflops": flops / (ours_ms * 1e-3) / 1e12,
            "ours_pct_of_bf16_peak": 100 * flops / (ours_ms * 1e-3) / 2.5e15,
            "ours_mem_beyond_inputs_MiB": ours_extra / 2**20}
+    # the same two calls replayed from a captured HIP graph (nothing in them allocates or synchronises):
+    # what the host side of the launches costs at short sequences
+    try:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(graph, stream=side):
+            ours()
+        torch.cuda.synchronize()
+        out["ours_graph_replay_ms"], _ = timed(graph.replay, args.steps, args.warmup, torch)
+    except RuntimeError as err:
+        out["ours_graph_replay_ms"] = None
+        out["ours_graph_replay_error"] = str(err)[:200]
 
     # ---- baselines
     logits_gib = args.hq * S * k * S * 2 / 2**30
